@@ -403,3 +403,32 @@ def test_full_round_is_the_composition(oracle):
     # the decoded update correlates positively with the true mean gradient
     gm = np.mean([g.astype(np.float64) for g in gs], axis=0)
     assert gd @ gm > 0
+
+
+def test_dither_and_eps_streams_do_not_collide(oracle):
+    """Distinct coordinates must draw distinct generator outputs: the number of equal 24-bit
+    values among n draws stays at the birthday level n^2 / 2^25, and lags that are natural
+    collision candidates of a wrong counter mapping (32, 128, 256, 4096) are uncorrelated."""
+    n = 1 << 15
+    u = oracle.dither_u(5, 9, 3, 0, np.arange(n))
+    dup = n - np.unique(u).size
+    assert dup < 4 * n * n / 2 ** 25 + 20
+    e = oracle.eps(5, 9, 3, np.arange(n))
+    for lag in (1, 2, 32, 64, 128, 256, 4096):
+        assert abs((u[:-lag] * u[lag:]).mean()) < 4.5 / 3.0 / math.sqrt(n - lag)
+        assert abs((e[:-lag] * e[lag:]).mean()) < 4.5 / math.sqrt(n - lag)
+
+
+def test_stream_layout_matches_the_stated_mapping(oracle):
+    """The coordinate -> (generator call, word, bits) mapping stated in the oracle's comments,
+    recomputed here from raw generator blocks: eps: call i>>7, word (i>>5)&3, bit i&31, set = -1;
+    dither: call ((i>>8)<<6)|(i&63), word (i>>6)&3, top 24 bits."""
+    seed, rnd, party = 0xABCDEF0123, 17, 6
+    for i in (0, 1, 31, 32, 63, 64, 127, 128, 255, 256, 1000, 65535, 65536, (1 << 25) + 12345):
+        w = oracle.rng(seed, oracle.DOMAIN_EPS, rnd, party, 0, i >> 7)
+        bit = (int(w[(i >> 5) & 3]) >> (i & 31)) & 1
+        assert oracle.eps(seed, rnd, party, [i])[0] == (-1.0 if bit else 1.0)
+        for k in (0, 2):
+            w = oracle.rng(seed, oracle.DOMAIN_DITHER, rnd, party, k, ((i >> 8) << 6) | (i & 63))
+            r = int(w[(i >> 6) & 3]) >> 8
+            assert oracle.dither_u(seed, rnd, party, k, [i])[0] == (2 * r + 1 - 2 ** 24) / 2 ** 24
