@@ -1,0 +1,140 @@
+/*
+ * fo.h -- C ABI of the MI355X (gfx950) FO-SGD gradient codec.
+ *
+ * Paper: "Flattened one-bit stochastic gradient descent", arXiv 2405.11095.  One FO-SGD
+ * iteration (Sec. 4) is: every worker n encodes its gradient g_n with the (eps_n, lambda)-encoder
+ * of Def. 3.7 and sends d sign bits; the server decodes each message with the decoder of
+ * Def. 3.8, averages (eq. "server average"), re-encodes the mean with the
+ * (eps^s, lambda^s, K)-encoder and sends it down; every worker decodes it and takes the step
+ * x <- x - delta * g^d.  This library is that codec.  The M workers are M buffers on one device.
+ *
+ * Conventions common to all calls
+ *   - Every pointer named "device" is a device (HBM) pointer owned by the caller.  The library
+ *     never frees or keeps them beyond the call's enqueued work.  float / uint64 device buffers
+ *     must be 16-byte aligned (FO_EALIGN otherwise).  Host pointers are said to be host.
+ *   - All work is enqueued on the caller's HIP stream (a hipStream_t passed as void*; NULL is the
+ *     default stream).  The hot calls (fo_encode, fo_decode, fo_server_aggregate, fo_step) do
+ *     not allocate, do not synchronise with the host and copy nothing between host and device;
+ *     scratch memory is allocated once by fo_plan_create.
+ *   - Return value: 0 (FO_OK) or a negative FO_E* code.  No exception crosses the boundary.
+ *   - A plan is not thread-safe; calls on one plan must not overlap on the device.
+ *   - Output buffers must not alias inputs (x in fo_step is updated in place by design).
+ *
+ * Geometry.  With block_log2 = 0 the transform length is n = max(64, 2^ceil(log2 d)) and the
+ * gradient is zero-padded to n (the paper assumes d a power of two, Def. 3.4).  With
+ * block_log2 = k the gradient is cut into ceil(d / 2^k) blocks of b = 2^k coordinates (the last
+ * zero-padded), each with its own transform and its own dither amplitude; the paper has no
+ * blocked variant, Lemma A.7 with gamma = 1/sqrt(b) is what covers it.  Padded length
+ * ntot = b * nblocks, packed words W = ntot / 64, scales per party = nblocks.
+ *
+ * Packed signs: word w, bit j  <->  coordinate 64 w + j; a set bit is +1.  sign(0) = +1.
+ *
+ * Scales.  A party's scales[j] is the dither amplitude lambda_j of block j in the paper's
+ * (orthonormal) normalisation: lambda = alpha * B * sqrt(ln b / b) (Thm 5.5), with B the caller's
+ * bound (FO_SCALE_BOUND) or the block's measured l2 norm (FO_SCALE_L2).  The server amplitude is
+ * lambda^s_j = alpha_s * max_n lambda_{n,j} * sqrt(ln b) (Thm 5.5).
+ *
+ * Random numbers.  eps and the dither are functions of (seed, round, party, coordinate) through
+ * Philox4x32-10; eps is therefore never transmitted, both ends regenerate it (the paper sends it
+ * explicitly, Sec. 4 "Transmission").  The dither is u * lambda with u an odd multiple of 2^-24
+ * in (-1, 1).
+ */
+#ifndef FO_H
+#define FO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FO_OK 0
+#define FO_EINVAL (-1) /* NULL / out-of-range argument, unsupported parameter value */
+#define FO_EALIGN (-2) /* a device pointer is not 16-byte aligned                      */
+#define FO_EHIP (-3)   /* a HIP runtime call failed; see fo_last_hip_error              */
+#define FO_ENOMEM (-4) /* plan creation could not allocate its scratch memory         */
+
+#define FO_DITHER_UNIFORM 0u /* tau ~ U[-lambda, lambda], Def. 3.2                       */
+#define FO_DITHER_NONE 1u    /* tau = 0: plain sign of the flattened vector (ablation)   */
+#define FO_SCALE_BOUND 0u    /* B is the caller's bound on ||g||_2 (Thm 5.5 verbatim)    */
+#define FO_SCALE_L2 1u       /* B := measured ||g_block||_2 at this call                 */
+#define FO_EPS_INDEPENDENT 0u /* one eps per worker and one for the server (Sec. 4)     */
+
+#define FO_PARTY_SERVER 0xFFFFFFFFu /* party id of the server; workers are 0 .. M-1      */
+#define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */
+
+#define FO_MAX_WORKERS 64u
+
+typedef struct {
+    uint64_t d;          /* logical gradient length, 1 <= d, padded length <= 2^30        */
+    uint32_t M;          /* number of workers (the paper's N), 1 .. FO_MAX_WORKERS        */
+    uint32_t block_log2; /* 0, or 6 .. 30                                                 */
+    uint32_t K;          /* averaging count of the downlink quantizer (Def. 3.2); only 1  */
+    uint32_t dither;     /* FO_DITHER_*                                                   */
+    uint32_t scale_rule; /* FO_SCALE_*                                                    */
+    uint32_t eps_mode;   /* FO_EPS_INDEPENDENT                                            */
+    float alpha;         /* worker amplitude factor, >= 2 (Lemma 3.6)                     */
+    float alpha_s;       /* server amplitude factor, >= 2                                 */
+    float B;             /* norm bound for FO_SCALE_BOUND, > 0 (ignored by FO_SCALE_L2)   */
+    uint64_t seed;
+} fo_params;
+
+typedef struct fo_plan fo_plan;
+
+/* Validates *params (host), copies it and allocates the plan's device scratch on the current
+ * device.  *out receives the plan (host object).  FO_EINVAL / FO_ENOMEM / FO_EHIP on failure. */
+int fo_plan_create(const fo_params *params, fo_plan **out);
+/* Frees the plan and its scratch.  The caller must have synchronised the streams it used. */
+void fo_plan_destroy(fo_plan *plan);
+
+size_t fo_padded_len(const fo_plan *plan);   /* ntot                                       */
+size_t fo_packed_words(const fo_plan *plan); /* W = ntot / 64                              */
+size_t fo_num_scales(const fo_plan *plan);   /* nblocks                                    */
+size_t fo_block_len(const fo_plan *plan);    /* b                                          */
+size_t fo_scratch_bytes(const fo_plan *plan);
+/* Text of the last HIP error seen by this library on the calling thread (host string). */
+const char *fo_last_hip_error(void);
+
+/* Encoder E_{eps,lambda}(g) = sign(H D_eps g + tau), Def. 3.7 with K = 1 (Sec. 4, "Encoding").
+ *   g       device fp32[len]: len = d for a worker, ntot when party == FO_PARTY_SERVER
+ *   round   iteration t; party: worker id < M, or FO_PARTY_SERVER
+ *   flags   0: scales[] is written with the amplitudes the rule gives;
+ *           FO_FORCE_SCALE: scales[] is read and used as given
+ *   bits    device uint64[W] out;  scales device fp32[nblocks] in or out                      */
+int fo_encode(fo_plan *plan, const float *g, uint64_t round, uint32_t party, uint32_t flags,
+              uint64_t *bits, float *scales, void *hip_stream);
+
+/* Decoder D_{eps,lambda}(q) = lambda D_eps H^T q, Def. 3.8 with K = 1 (Sec. 4, "Decoding").
+ *   bits device uint64[W], scales device fp32[nblocks] (as produced by the matching encode)
+ *   out  device fp32[d]: the first d coordinates of the decoded vector                          */
+int fo_decode(fo_plan *plan, const uint64_t *bits, const float *scales, uint64_t round,
+              uint32_t party, float *out, void *hip_stream);
+
+/* Server: gbar = (1/M) sum_n D_{eps_n,lambda_n}(q_n) (eq. "server average"), then the
+ * (eps^s, lambda^s)-encoder applied to gbar in R^ntot (Sec. 4, "Server-to-workers").
+ *   bits_up     device uint64[M][W];   scales_up   device fp32[M][nblocks]
+ *   bits_down   device uint64[W] out;  scales_down device fp32[nblocks] out (lambda^s)
+ *   gbar_or_null  optional device fp32[ntot] out: the mean, materialised (for checking)         */
+int fo_server_aggregate(fo_plan *plan, const uint64_t *bits_up, const float *scales_up,
+                        uint64_t round, uint64_t *bits_down, float *scales_down,
+                        float *gbar_or_null, void *hip_stream);
+
+/* One whole iteration (Sec. 4, "At iteration t"): M encodes, server, one downlink decode and
+ * x <- x - delta * g^d (eq. "workers update").  Gives the same bits and the same x as the three
+ * calls above made by hand followed by the update.
+ *   g   HOST array of M device pointers, each fp32[d];  x device fp32[d], updated in place
+ * The intermediate messages stay in plan scratch; fo_step_messages exposes them.               */
+int fo_step(fo_plan *plan, const float *const *g, float *x, float delta, uint64_t round,
+            void *hip_stream);
+
+/* Device pointers into plan scratch holding the messages of the last fo_step on this plan:
+ * bits_up [M][W], scales_up [M][nblocks], bits_down [W], scales_down [nblocks].  Any out
+ * argument may be NULL.  Valid until the next hot call on the plan. */
+int fo_step_messages(fo_plan *plan, const uint64_t **bits_up, const float **scales_up,
+                     const uint64_t **bits_down, const float **scales_down);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FO_H */

@@ -95,9 +95,16 @@ void orc_rng(uint64_t seed, uint32_t domain, uint64_t round, uint32_t party, uin
  * (i mod 32) of word ((i / 32) mod 4) of call (i / 128); a set bit means eps_i = -1. */
 int orc_eps(uint64_t seed, uint64_t round, uint32_t eps_party, uint64_t i)
 {
-    uint32_t w[4];
-    orc_rng(seed, ORC_DOMAIN_EPS, round, eps_party, 0, (uint32_t)(i >> 7), w);
-    return ((w[(i >> 5) & 3] >> (i & 31)) & 1u) ? -1 : +1;
+    /* the last generator block is remembered per thread: consecutive coordinates share it */
+    static _Thread_local struct { int valid; uint64_t seed, round; uint32_t party, counter, w[4]; } memo;
+    uint32_t counter = (uint32_t)(i >> 7);
+    if (!memo.valid || memo.seed != seed || memo.round != round || memo.party != eps_party ||
+        memo.counter != counter) {
+        orc_rng(seed, ORC_DOMAIN_EPS, round, eps_party, 0, counter, memo.w);
+        memo.valid = 1; memo.seed = seed; memo.round = round; memo.party = eps_party;
+        memo.counter = counter;
+    }
+    return ((memo.w[(i >> 5) & 3] >> (i & 31)) & 1u) ? -1 : +1;
 }
 
 /* u_i in (-1,1) so that tau_i = lambda * u_i (Def. 3.2): one generator call covers the four
@@ -235,25 +242,29 @@ double orc_lambda(double alpha, double B, uint64_t n)
     return alpha * B * sqrt(log((double)n) / (double)n);
 }
 
-/* E_{eps,lambda,K}(x) = (K/lambda) Q_{lambda,K}(H_eps x), per block.
- *   x      [d]     input (already double)
- *   lam    [nb]    force != 0: amplitudes to use; else written with the rule's value, where B is
- *                  p->B (BOUND) or the block's own l2 norm (L2)
- *   q      [ntot]  integer code; bits [ntot/64] packed signs when K == 1 (may be NULL)
- *   margin [ntot]  optional z_i + tau_i;  z_out [ntot] optional flattened vector H_eps x */
-void orc_encode(const orc_params *p, const double *x, uint64_t round, uint32_t party, uint32_t K,
-                int force, double *lam, int32_t *q, uint64_t *bits, double *margin, double *z_out)
+/* E_{eps,lambda,K}(x) = (K/lambda) Q_{lambda,K}(H_eps x), per block, for blocks j0 .. j0+nj-1.
+ * Blocks are independent, so a range of them can be encoded alone; every array below covers
+ * that range only and is indexed from its first coordinate (block j0, coordinate j0*b).
+ *   xs     input slice (already double): coordinates j0*b .. min(d, (j0+nj)*b) - 1
+ *   lam    [nj]      force != 0: amplitudes to use; else written with the rule's value, where B
+ *                    is p->B (BOUND) or the block's own l2 norm (L2)
+ *   q      [nj*b]    integer code; bits [nj*b/64] packed signs when K == 1 (may be NULL)
+ *   margin [nj*b]    optional z_i + tau_i;  z_out [nj*b] optional flattened vector H_eps x */
+void orc_encode_blocks(const orc_params *p, const double *xs, uint64_t round, uint32_t party,
+                       uint32_t K, int force, uint64_t j0, uint64_t nj, double *lam, int32_t *q,
+                       uint64_t *bits, double *margin, double *z_out)
 {
     uint64_t b, nb, ntot;
     orc_geometry(p, &b, &nb, &ntot);
     uint32_t ep = eps_party_of(p->eps_mode, party);
     double *y = (double *)malloc(b * sizeof(double));
     double rs = 1.0 / sqrt((double)b);
-    for (uint64_t j = 0; j < nb; ++j) {
+    for (uint64_t jj = 0; jj < nj; ++jj) {
+        uint64_t first = (j0 + jj) * b;                          /* global index of the block */
         double ss = 0.0;
         for (uint64_t l = 0; l < b; ++l) {
-            uint64_t i = j * b + l;
-            double v = (i < p->d) ? x[i] : 0.0;
+            uint64_t i = first + l;
+            double v = (i < p->d) ? xs[jj * b + l] : 0.0;        /* zero padding beyond d */
             ss += v * v;
             y[l] = v * (double)orc_eps(p->seed, round, ep, i);   /* D_eps x */
         }
@@ -261,33 +272,50 @@ void orc_encode(const orc_params *p, const double *x, uint64_t round, uint32_t p
         for (uint64_t l = 0; l < b; ++l) y[l] *= rs;             /* H = calH / sqrt(b) */
         if (!force) {
             double B = (p->scale_rule == ORC_SCALE_BOUND) ? p->B : sqrt(ss);
-            lam[j] = orc_lambda(p->alpha, B, b);
+            lam[jj] = orc_lambda(p->alpha, B, b);
         }
-        orc_quantize(y, b, j * b, lam[j], K, p->dither, p->seed, round, party, q + j * b,
-                     margin ? margin + j * b : NULL);
-        if (z_out) memcpy(z_out + j * b, y, b * sizeof(double));
+        orc_quantize(y, b, first, lam[jj], K, p->dither, p->seed, round, party, q + jj * b,
+                     margin ? margin + jj * b : NULL);
+        if (z_out) memcpy(z_out + jj * b, y, b * sizeof(double));
     }
-    if (bits && K == 1) orc_pack(q, ntot, bits);
+    if (bits && K == 1) orc_pack(q, nj * b, bits);
     free(y);
 }
 
-/* D_{eps,lambda,K}(q) = (lambda/K) D_eps H^T q, per block; out has ntot entries (no truncation). */
-void orc_decode(const orc_params *p, const int32_t *q, const double *lam, uint32_t K,
-                uint64_t round, uint32_t party, double *out)
+void orc_encode(const orc_params *p, const double *x, uint64_t round, uint32_t party, uint32_t K,
+                int force, double *lam, int32_t *q, uint64_t *bits, double *margin, double *z_out)
+{
+    uint64_t b, nb, ntot;
+    orc_geometry(p, &b, &nb, &ntot);
+    orc_encode_blocks(p, x, round, party, K, force, 0, nb, lam, q, bits, margin, z_out);
+}
+
+/* D_{eps,lambda,K}(q) = (lambda/K) D_eps H^T q, per block, for blocks j0 .. j0+nj-1; q [nj*b],
+ * lam [nj] and out [nj*b] cover that range only (no truncation to d). */
+void orc_decode_blocks(const orc_params *p, const int32_t *q, const double *lam, uint32_t K,
+                       uint64_t round, uint32_t party, uint64_t j0, uint64_t nj, double *out)
 {
     uint64_t b, nb, ntot;
     orc_geometry(p, &b, &nb, &ntot);
     uint32_t ep = eps_party_of(p->eps_mode, party);
     double rs = 1.0 / sqrt((double)b);
-    for (uint64_t j = 0; j < nb; ++j) {
-        double *y = out + j * b;
-        for (uint64_t l = 0; l < b; ++l) y[l] = (double)q[j * b + l];
+    for (uint64_t jj = 0; jj < nj; ++jj) {
+        double *y = out + jj * b;
+        for (uint64_t l = 0; l < b; ++l) y[l] = (double)q[jj * b + l];
         orc_fwht(y, b);                                          /* H^T = H (symmetric) */
         for (uint64_t l = 0; l < b; ++l) {
-            uint64_t i = j * b + l;
-            y[l] = (lam[j] / (double)K) * (double)orc_eps(p->seed, round, ep, i) * (y[l] * rs);
+            uint64_t i = (j0 + jj) * b + l;
+            y[l] = (lam[jj] / (double)K) * (double)orc_eps(p->seed, round, ep, i) * (y[l] * rs);
         }
     }
+}
+
+void orc_decode(const orc_params *p, const int32_t *q, const double *lam, uint32_t K,
+                uint64_t round, uint32_t party, double *out)
+{
+    uint64_t b, nb, ntot;
+    orc_geometry(p, &b, &nb, &ntot);
+    orc_decode_blocks(p, q, lam, K, round, party, 0, nb, out);
 }
 
 /* ------------------------------------------------------------------------------------------ */

@@ -182,6 +182,35 @@ def encode(p: Params, x, rnd, party, K=1, lam=None, want_margin=False, want_z=Fa
     return dict(q=q, bits=bits, lam=lam_a, margin=margin, z=z)
 
 
+def encode_blocks(p: Params, xs, rnd, party, j0, nj, K=1, lam=None, want_margin=False):
+    """Encode blocks j0 .. j0+nj-1 only; xs is the input slice starting at coordinate j0*b."""
+    b, nb, nt = geometry(p)
+    xs = _f64(xs)
+    assert j0 + nj <= nb and xs.size == min(p.d, (j0 + nj) * b) - j0 * b
+    force = lam is not None
+    lam_a = _f64(lam).copy() if force else np.zeros(nj, dtype=np.float64)
+    q = np.zeros(nj * b, dtype=np.int32)
+    bits = np.zeros(nj * b // 64, dtype=np.uint64) if K == 1 else None
+    margin = np.zeros(nj * b, dtype=np.float64) if want_margin else None
+    lib().orc_encode_blocks(C.byref(p), _p(xs, C.c_double), C.c_uint64(rnd), C.c_uint32(party),
+                            C.c_uint32(K), C.c_int(1 if force else 0), C.c_uint64(j0), C.c_uint64(nj),
+                            _p(lam_a, C.c_double), _p(q, C.c_int32), _p(bits, C.c_uint64),
+                            _p(margin, C.c_double), None)
+    return dict(q=q, bits=bits, lam=lam_a, margin=margin)
+
+
+def decode_blocks(p: Params, q, lam, rnd, party, j0, nj, K=1):
+    b, nb, nt = geometry(p)
+    q = np.ascontiguousarray(q, dtype=np.int32)
+    lam = _f64(lam)
+    assert q.size == nj * b and lam.size == nj
+    out = np.zeros(nj * b, dtype=np.float64)
+    lib().orc_decode_blocks(C.byref(p), _p(q, C.c_int32), _p(lam, C.c_double), C.c_uint32(K),
+                            C.c_uint64(rnd), C.c_uint32(party), C.c_uint64(j0), C.c_uint64(nj),
+                            _p(out, C.c_double))
+    return out
+
+
 def decode(p: Params, q, lam, rnd, party, K=1):
     """Decoded vector of padded length ntot (fp64); callers truncate to d."""
     b, nb, nt = geometry(p)

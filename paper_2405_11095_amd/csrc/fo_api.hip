@@ -1,0 +1,474 @@
+// C ABI of the FO-SGD codec (declared in include/fo.h): argument checks, plan scratch and kernel
+// launch sequences.  Every step of the codec runs in the kernels of fo_contig.h / fo_strided.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <type_traits>
+
+#include "../../include/fo.h"
+#include "fo_strided.h"
+
+using namespace fo;
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+bool hip_ok(hipError_t e, const char *what)
+{
+    if (e == hipSuccess) return true;
+    std::snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
+    return false;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small kernels
+// ---------------------------------------------------------------------------------------------
+
+// lambda_j = coef * sqrt(sum of the tile partials of block j)   (amplitude of Thm 5.5, B = ||g_block||)
+__global__ __launch_bounds__(256) void k_finalize_scales(const float *partials, uint64_t ntiles, uint32_t tiles_per_block,
+                                                          float coef, float *scales, uint64_t scales_stride)
+{
+    __shared__ double red[256];
+    const uint32_t j = blockIdx.x, slot = blockIdx.y, t = threadIdx.x;
+    const float *p = partials + (uint64_t)slot * ntiles + (uint64_t)j * tiles_per_block;
+    double s = 0.0;
+    for (uint32_t k = t; k < tiles_per_block; k += 256) s += (double)p[k];
+    red[t] = s;
+    __syncthreads();
+    for (uint32_t h = 128; h > 0; h >>= 1) {
+        if (t < h) red[t] += red[t + h];
+        __syncthreads();
+    }
+    if (t == 0) scales[slot * scales_stride + j] = coef * (float)sqrt(red[0]);
+}
+
+__global__ void k_fill_scales(float *scales, uint64_t scales_stride, uint64_t nblocks, float value)
+{
+    const uint64_t j = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (j < nblocks) scales[blockIdx.y * scales_stride + j] = value;
+}
+
+// lambda^s_j = coef_s * max_n lambda_{n,j}   (Thm 5.5: lambda^s = alpha_s * lambda * sqrt(log n))
+__global__ void k_server_scales(const float *scales_up, uint64_t nblocks, uint32_t M, float coef_s, float *scales_down)
+{
+    const uint64_t j = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (j >= nblocks) return;
+    float m = 0.f;
+    bool nan = false;
+    for (uint32_t n = 0; n < M; ++n) {
+        const float l = scales_up[(uint64_t)n * nblocks + j];
+        nan |= (l != l);
+        m = fmaxf(m, l);
+    }
+    scales_down[j] = nan ? __builtin_nanf("") : coef_s * m;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+} // namespace
+
+// ---------------------------------------------------------------------------------------------
+// Plan
+// ---------------------------------------------------------------------------------------------
+struct fo_plan {
+    fo_params p;
+    uint32_t logb;       // log2 of the transform length
+    uint64_t b, nblocks, ntot, W, ntiles;
+    uint32_t S;          // stages done by the contiguous kernel
+    uint32_t npass;      // strided passes: 0, 1 or 2
+    uint32_t hb[2];      // stages of each strided pass (pass 0 is adjacent to the contiguous tile)
+    float coef_lambda, sqrtb, rsqrtb, coef_s;
+    // scratch (device)
+    char *scratch;
+    size_t scratch_bytes;
+    float *buf_a;        // [M][ntot] 4-byte intermediates (transform lengths above 2^15)
+    float *buf_b;        // [ntot] mean gradient / server intermediate
+    float *buf_c;        // [ntot] second intermediate for three-pass transforms, else NULL
+    float *partials;     // [M][ntiles]
+    uint64_t *bits_up;   // [M][W]
+    float *scales_up;    // [M][nblocks]
+    uint64_t *bits_down; // [W]
+    float *scales_down;  // [nblocks]
+};
+
+extern "C" const char *fo_last_hip_error(void) { return g_hip_err; }
+
+extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
+{
+    if (!params || !out) return FO_EINVAL;
+    *out = nullptr;
+    const fo_params &q = *params;
+    if (q.d < 1 || q.M < 1 || q.M > FO_MAX_WORKERS) return FO_EINVAL;
+    if (q.block_log2 != 0 && (q.block_log2 < 6 || q.block_log2 > 30)) return FO_EINVAL;
+    if (q.K != 1) return FO_EINVAL;
+    if (q.dither != FO_DITHER_UNIFORM && q.dither != FO_DITHER_NONE) return FO_EINVAL;
+    if (q.scale_rule != FO_SCALE_BOUND && q.scale_rule != FO_SCALE_L2) return FO_EINVAL;
+    if (q.eps_mode != FO_EPS_INDEPENDENT) return FO_EINVAL;
+    if (!(q.alpha >= 2.f) || !(q.alpha_s >= 2.f)) return FO_EINVAL;
+    if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
+
+    fo_plan *pl = new (std::nothrow) fo_plan();
+    if (!pl) return FO_ENOMEM;
+    pl->p = q;
+    if (q.block_log2 == 0) {
+        uint32_t k = 6;
+        while (((uint64_t)1 << k) < q.d) ++k;
+        if (k > 30) { delete pl; return FO_EINVAL; }
+        pl->logb = k;
+        pl->nblocks = 1;
+    } else {
+        pl->logb = q.block_log2;
+        pl->nblocks = (q.d + (((uint64_t)1 << pl->logb) - 1)) >> pl->logb;
+    }
+    pl->b = (uint64_t)1 << pl->logb;
+    pl->ntot = pl->b * pl->nblocks;
+    if (pl->ntot > ((uint64_t)1 << 32)) { delete pl; return FO_EINVAL; }
+    pl->W = pl->ntot / 64;
+    pl->ntiles = (pl->ntot + kTile - 1) / kTile;
+    pl->S = pl->logb < (uint32_t)kTileLog2 ? pl->logb : (uint32_t)kTileLog2;
+    const uint32_t high = pl->logb - pl->S;
+    pl->npass = high == 0 ? 0 : (high <= 10 ? 1 : 2);
+    pl->hb[0] = pl->npass == 2 ? (high + 1) / 2 : high;
+    pl->hb[1] = high - pl->hb[0];
+    const double bd = (double)pl->b;
+    pl->coef_lambda = (float)((double)q.alpha * std::sqrt(std::log(bd) / bd));
+    pl->sqrtb = (float)std::sqrt(bd);
+    pl->rsqrtb = (float)(1.0 / std::sqrt(bd));
+    pl->coef_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd)));
+
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t sz_a = pl->npass ? up((size_t)q.M * pl->ntot * 4) : 0;
+    const size_t sz_b = up(pl->ntot * 4);
+    const size_t sz_c = pl->npass == 2 ? up(pl->ntot * 4) : 0;
+    const size_t sz_part = up((size_t)q.M * pl->ntiles * 4);
+    const size_t sz_bu = up((size_t)q.M * pl->W * 8), sz_su = up((size_t)q.M * pl->nblocks * 4);
+    const size_t sz_bd = up(pl->W * 8), sz_sd = up(pl->nblocks * 4);
+    pl->scratch_bytes = sz_a + sz_b + sz_c + sz_part + sz_bu + sz_su + sz_bd + sz_sd;
+    void *mem = nullptr;
+    hipError_t e = hipMalloc(&mem, pl->scratch_bytes);
+    if (e != hipSuccess) {
+        hip_ok(e, "hipMalloc(plan scratch)");
+        delete pl;
+        return e == hipErrorOutOfMemory ? FO_ENOMEM : FO_EHIP;
+    }
+    char *c = static_cast<char *>(mem);
+    pl->scratch = c;
+    pl->buf_a = sz_a ? reinterpret_cast<float *>(c) : nullptr; c += sz_a;
+    pl->buf_b = reinterpret_cast<float *>(c); c += sz_b;
+    pl->buf_c = sz_c ? reinterpret_cast<float *>(c) : nullptr; c += sz_c;
+    pl->partials = reinterpret_cast<float *>(c); c += sz_part;
+    pl->bits_up = reinterpret_cast<uint64_t *>(c); c += sz_bu;
+    pl->scales_up = reinterpret_cast<float *>(c); c += sz_su;
+    pl->bits_down = reinterpret_cast<uint64_t *>(c); c += sz_bd;
+    pl->scales_down = reinterpret_cast<float *>(c);
+    *out = pl;
+    return FO_OK;
+}
+
+extern "C" void fo_plan_destroy(fo_plan *plan)
+{
+    if (!plan) return;
+    if (plan->scratch) (void)hipFree(plan->scratch);
+    delete plan;
+}
+
+extern "C" size_t fo_padded_len(const fo_plan *p) { return p ? p->ntot : 0; }
+extern "C" size_t fo_packed_words(const fo_plan *p) { return p ? p->W : 0; }
+extern "C" size_t fo_num_scales(const fo_plan *p) { return p ? p->nblocks : 0; }
+extern "C" size_t fo_block_len(const fo_plan *p) { return p ? p->b : 0; }
+extern "C" size_t fo_scratch_bytes(const fo_plan *p) { return p ? p->scratch_bytes : 0; }
+
+// ---------------------------------------------------------------------------------------------
+// Launch sequences
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+struct Rng {
+    uint32_t k0, k1, round_lo;
+};
+Rng rng_of(const fo_plan *pl, uint64_t round)
+{
+    return { (uint32_t)pl->p.seed, (uint32_t)(pl->p.seed >> 32) ^ (uint32_t)(round >> 32), (uint32_t)round };
+}
+
+#define FO_LAUNCH_CHECK(what)                                                       \
+    do {                                                                            \
+        if (!hip_ok(hipGetLastError(), what)) return FO_EHIP;                       \
+    } while (0)
+
+StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
+{
+    StridedArgs s;
+    std::memset(&s, 0, sizeof(s));
+    s.hb = pl->hb[pass];
+    s.ls = pass == 0 ? (uint32_t)kTileLog2 : (uint32_t)kTileLog2 + pl->hb[0];
+    s.logb = pl->logb;
+    s.k0 = r.k0; s.k1 = r.k1; s.round_lo = r.round_lo;
+    s.len_in = s.len_out = pl->ntot;
+    return s;
+}
+
+ContigArgs contig_base(const fo_plan *pl, const Rng &r)
+{
+    ContigArgs c;
+    std::memset(&c, 0, sizeof(c));
+    c.W = pl->W;
+    c.nblocks = pl->nblocks;
+    c.S = pl->S;
+    c.logb = pl->logb;
+    c.dither = pl->p.dither;
+    c.k0 = r.k0; c.k1 = r.k1; c.round_lo = r.round_lo;
+    c.coef_lambda = pl->coef_lambda;
+    c.sqrtb = pl->sqrtb;
+    c.len_in = c.len_out = pl->ntot;
+    return c;
+}
+
+// Encode `nslots` vectors.  Sources: tab (pointer table, nslots entries) or src + slot * src_stride.
+// mode 0: amplitudes from the measured norm; 1: scales[] already holds them (forced / bound rule).
+int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src_stride, uint64_t len_in,
+                  uint32_t nslots, uint32_t party0, uint64_t round, bool scales_given, uint64_t *bits,
+                  uint64_t bits_stride, float *scales, uint64_t scales_stride, float *tmp, uint64_t tmp_stride,
+                  hipStream_t st)
+{
+    const Rng r = rng_of(pl, round);
+    PtrTab none;
+    std::memset(&none, 0, sizeof(none));
+    const PtrTab &tb = tab ? *tab : none;
+    const dim3 grid((unsigned)pl->ntiles, nslots), block(kThreads);
+    ContigArgs c = contig_base(pl, r);
+    c.dst = bits; c.dst_stride = bits_stride;
+    c.scales = scales; c.scales_stride = scales_stride;
+    c.party0 = party0; c.eps_party0 = party0;
+    if (pl->npass == 0) {
+        c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
+        c.len_in = len_in;
+        c.compute_scale = scales_given ? 0u : 1u;
+        hipLaunchKernelGGL((k_contig<IN_GRAD, OUT_PACK>), grid, block, 0, st, c, tb);
+        FO_LAUNCH_CHECK("k_contig<IN_GRAD,OUT_PACK>");
+        return FO_OK;
+    }
+    // transform lengths above 2^15: high stages first (eps flip and norm on load), low stages last
+    const uint32_t first = pl->npass - 1;
+    StridedArgs s = strided_base(pl, r, first);
+    s.src = src; s.src_stride = src_stride; s.use_tab = tab ? 1u : 0u; s.len_in = len_in;
+    s.dst = (pl->npass == 2) ? pl->buf_c : tmp; s.dst_stride = (pl->npass == 2) ? 0 : tmp_stride;
+    s.partials = pl->partials; s.eps_party0 = party0;
+    if (pl->npass == 2 && nslots != 1) return FO_EINVAL; // three-pass transforms are encoded one party at a time
+    hipLaunchKernelGGL((k_strided<SM_ENC_FIRST>), grid, block, 0, st, s, tb);
+    FO_LAUNCH_CHECK("k_strided<ENC_FIRST>");
+    if (pl->npass == 2) {
+        StridedArgs s2 = strided_base(pl, r, 0);
+        s2.src = pl->buf_c; s2.dst = tmp; s2.src_stride = 0; s2.dst_stride = tmp_stride;
+        hipLaunchKernelGGL((k_strided<SM_MID_F32>), grid, block, 0, st, s2, none);
+        FO_LAUNCH_CHECK("k_strided<MID_F32>");
+    }
+    if (!scales_given) {
+        hipLaunchKernelGGL(k_finalize_scales, dim3((unsigned)pl->nblocks, nslots), dim3(256), 0, st, pl->partials,
+                           pl->ntiles, (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda, scales, scales_stride);
+        FO_LAUNCH_CHECK("k_finalize_scales");
+    }
+    c.src = tmp; c.src_stride = tmp_stride;
+    hipLaunchKernelGGL((k_contig<IN_F32, OUT_PACK>), grid, block, 0, st, c, none);
+    FO_LAUNCH_CHECK("k_contig<IN_F32,OUT_PACK>");
+    return FO_OK;
+}
+
+// Decode one party into out[len_out] with the given store mode.
+int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64_t round, uint32_t party,
+                  float *out, uint64_t len_out, uint32_t store_mode, float out_coef, float delta, float *tmp,
+                  hipStream_t st)
+{
+    const Rng r = rng_of(pl, round);
+    PtrTab none;
+    std::memset(&none, 0, sizeof(none));
+    const dim3 grid((unsigned)pl->ntiles, 1), block(kThreads);
+    ContigArgs c = contig_base(pl, r);
+    c.src = bits; c.src_stride = 0;
+    c.scales = const_cast<float *>(scales); c.scales_stride = 0;
+    c.party0 = party; c.eps_party0 = party;
+    if (pl->npass == 0) {
+        c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
+        hipLaunchKernelGGL((k_contig<IN_BITS, OUT_F32>), grid, block, 0, st, c, none);
+        FO_LAUNCH_CHECK("k_contig<IN_BITS,OUT_F32>");
+        return FO_OK;
+    }
+    c.dst = tmp; c.dst_stride = 0;
+    hipLaunchKernelGGL((k_contig<IN_BITS, OUT_I32>), grid, block, 0, st, c, none);
+    FO_LAUNCH_CHECK("k_contig<IN_BITS,OUT_I32>");
+    const void *cur = tmp;
+    if (pl->npass == 2) {
+        StridedArgs s1 = strided_base(pl, r, 0);
+        s1.src = tmp; s1.dst = pl->buf_c;
+        hipLaunchKernelGGL((k_strided<SM_MID_I32>), grid, block, 0, st, s1, none);
+        FO_LAUNCH_CHECK("k_strided<MID_I32>");
+        cur = pl->buf_c;
+    }
+    StridedArgs s = strided_base(pl, r, pl->npass - 1);
+    s.src = cur; s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
+    s.scales = scales; s.scales_stride = 0; s.eps_party0 = party;
+    hipLaunchKernelGGL((k_strided<SM_DEC_LAST>), grid, block, 0, st, s, none);
+    FO_LAUNCH_CHECK("k_strided<DEC_LAST>");
+    return FO_OK;
+}
+
+int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, uint64_t round, uint64_t *bits_down,
+                  float *scales_down, float *gbar_or_null, hipStream_t st)
+{
+    const Rng r = rng_of(pl, round);
+    const uint32_t M = pl->p.M;
+    PtrTab none;
+    std::memset(&none, 0, sizeof(none));
+    hipLaunchKernelGGL(k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), 0, st, scales_up,
+                       pl->nblocks, M, pl->coef_s, scales_down);
+    FO_LAUNCH_CHECK("k_server_scales");
+    const float mean_coef = pl->rsqrtb / (float)M;
+    if (pl->npass == 0) {
+        // decode every worker into the mean (materialised), then encode the mean
+        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
+        for (uint32_t m = 0; m < M; ++m) {
+            int rc = launch_decode(pl, bits_up + (uint64_t)m * pl->W, scales_up + (uint64_t)m * pl->nblocks, round, m, gbar,
+                                   pl->ntot, m == 0 ? STORE_SET : STORE_ACC, mean_coef, 0.f, nullptr, st);
+            if (rc) return rc;
+        }
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
+                             nullptr, 0, st);
+    }
+    if (pl->npass == 2) {
+        // three-pass transforms: unfused (decode each worker into the mean, then a plain encode)
+        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
+        for (uint32_t m = 0; m < M; ++m) {
+            int rc = launch_decode(pl, bits_up + (uint64_t)m * pl->W, scales_up + (uint64_t)m * pl->nblocks, round, m, gbar,
+                                   pl->ntot, m == 0 ? STORE_SET : STORE_ACC, mean_coef, 0.f, pl->buf_a, st);
+            if (rc) return rc;
+        }
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
+                             pl->buf_a, 0, st);
+    }
+    // two-pass transforms: M low-stage passes (bits -> int32), one fused high-stage pass that forms the mean
+    // and starts the re-encode, one low-stage pass that dithers and packs
+    {
+        ContigArgs c = contig_base(pl, r);
+        c.src = bits_up; c.src_stride = pl->W;
+        c.dst = pl->buf_a; c.dst_stride = pl->ntot;
+        hipLaunchKernelGGL((k_contig<IN_BITS, OUT_I32>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), 0, st, c, none);
+        FO_LAUNCH_CHECK("k_contig<IN_BITS,OUT_I32> (server)");
+    }
+    {
+        StridedArgs s = strided_base(pl, r, 0);
+        s.src = pl->buf_a; s.src_stride = pl->ntot;
+        s.dst = pl->buf_b;
+        s.scales = scales_up; s.scales_stride = pl->nblocks;
+        s.gbar = gbar_or_null;
+        s.M = M; s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
+        hipLaunchKernelGGL((k_strided<SM_SERVER>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), 0, st, s, none);
+        FO_LAUNCH_CHECK("k_strided<SERVER>");
+    }
+    {
+        ContigArgs c = contig_base(pl, r);
+        c.src = pl->buf_b; c.src_stride = 0;
+        c.dst = bits_down; c.dst_stride = 0;
+        c.scales = scales_down; c.scales_stride = 0;
+        c.party0 = FO_PARTY_SERVER; c.eps_party0 = FO_PARTY_SERVER;
+        hipLaunchKernelGGL((k_contig<IN_F32, OUT_PACK>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), 0, st, c, none);
+        FO_LAUNCH_CHECK("k_contig<IN_F32,OUT_PACK> (server)");
+    }
+    return FO_OK;
+}
+
+int prepare_scales(fo_plan *pl, uint32_t nslots, bool forced, float *scales, uint64_t scales_stride, hipStream_t st,
+                   bool *given)
+{
+    *given = forced;
+    if (!forced && pl->p.scale_rule == FO_SCALE_BOUND) {
+        hipLaunchKernelGGL(k_fill_scales, dim3((unsigned)((pl->nblocks + 255) / 256), nslots), dim3(256), 0, st, scales,
+                           scales_stride, pl->nblocks, pl->coef_lambda * pl->p.B);
+        FO_LAUNCH_CHECK("k_fill_scales");
+        *given = true;
+    }
+    return FO_OK;
+}
+
+} // namespace
+
+extern "C" int fo_encode(fo_plan *pl, const float *g, uint64_t round, uint32_t party, uint32_t flags, uint64_t *bits,
+                         float *scales, void *hip_stream)
+{
+    if (!pl || !g || !bits || !scales) return FO_EINVAL;
+    if (party != FO_PARTY_SERVER && party >= pl->p.M) return FO_EINVAL;
+    if (flags & ~FO_FORCE_SCALE) return FO_EINVAL;
+    if (!aligned16(g) || !aligned16(bits) || !aligned16(scales)) return FO_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    bool given;
+    int rc = prepare_scales(pl, 1, (flags & FO_FORCE_SCALE) != 0, scales, 0, st, &given);
+    if (rc) return rc;
+    const uint64_t len = party == FO_PARTY_SERVER ? pl->ntot : pl->p.d;
+    return launch_encode(pl, nullptr, g, 0, len, 1, party, round, given, bits, 0, scales, 0, pl->buf_a, 0, st);
+}
+
+extern "C" int fo_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64_t round, uint32_t party,
+                         float *out, void *hip_stream)
+{
+    if (!pl || !bits || !scales || !out) return FO_EINVAL;
+    if (party != FO_PARTY_SERVER && party >= pl->p.M) return FO_EINVAL;
+    if (!aligned16(bits) || !aligned16(scales) || !aligned16(out)) return FO_EALIGN;
+    return launch_decode(pl, bits, scales, round, party, out, pl->p.d, STORE_SET, pl->rsqrtb, 0.f, pl->buf_a,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int fo_server_aggregate(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, uint64_t round,
+                                   uint64_t *bits_down, float *scales_down, float *gbar_or_null, void *hip_stream)
+{
+    if (!pl || !bits_up || !scales_up || !bits_down || !scales_down) return FO_EINVAL;
+    if (!aligned16(bits_up) || !aligned16(scales_up) || !aligned16(bits_down) || !aligned16(scales_down) ||
+        !aligned16(gbar_or_null))
+        return FO_EALIGN;
+    return launch_server(pl, bits_up, scales_up, round, bits_down, scales_down, gbar_or_null,
+                         static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta, uint64_t round, void *hip_stream)
+{
+    if (!pl || !g || !x) return FO_EINVAL;
+    if (!aligned16(x)) return FO_EALIGN;
+    PtrTab tab;
+    std::memset(&tab, 0, sizeof(tab));
+    for (uint32_t m = 0; m < pl->p.M; ++m) {
+        if (!g[m]) return FO_EINVAL;
+        if (!aligned16(g[m])) return FO_EALIGN;
+        tab.p[m] = g[m];
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint32_t M = pl->p.M;
+    bool given;
+    int rc = prepare_scales(pl, M, false, pl->scales_up, pl->nblocks, st, &given);
+    if (rc) return rc;
+    if (pl->npass == 2) {
+        for (uint32_t m = 0; m < M && !rc; ++m)
+            rc = launch_encode(pl, nullptr, g[m], 0, pl->p.d, 1, m, round, given, pl->bits_up + (uint64_t)m * pl->W, 0,
+                               pl->scales_up + (uint64_t)m * pl->nblocks, 0, pl->buf_a, 0, st);
+    } else {
+        rc = launch_encode(pl, &tab, nullptr, 0, pl->p.d, M, 0, round, given, pl->bits_up, pl->W, pl->scales_up,
+                           pl->nblocks, pl->buf_a, pl->ntot, st);
+    }
+    if (rc) return rc;
+    rc = launch_server(pl, pl->bits_up, pl->scales_up, round, pl->bits_down, pl->scales_down, nullptr, st);
+    if (rc) return rc;
+    return launch_decode(pl, pl->bits_down, pl->scales_down, round, FO_PARTY_SERVER, x, pl->p.d, STORE_AXPY, pl->rsqrtb,
+                         delta, pl->buf_a, st);
+}
+
+extern "C" int fo_step_messages(fo_plan *pl, const uint64_t **bits_up, const float **scales_up,
+                                const uint64_t **bits_down, const float **scales_down)
+{
+    if (!pl) return FO_EINVAL;
+    if (bits_up) *bits_up = pl->bits_up;
+    if (scales_up) *scales_up = pl->scales_up;
+    if (bits_down) *bits_down = pl->bits_down;
+    if (scales_down) *scales_down = pl->scales_down;
+    return FO_OK;
+}

@@ -1,0 +1,299 @@
+// Contiguous-tile kernel: the low min(log2 b, 15) Walsh-Hadamard stages of every 2^15-coordinate
+// tile, fused with whatever sits at either end of the transform:
+//   input  : fp32 gradient (zero-padded) with the eps sign flip and the per-block sum of squares
+//            (Def. 3.5; norm for the amplitude of Thm 5.5) | fp32 intermediate | packed sign bits
+//   output : dither + sign + 64-bit packing (Def. 3.2, Def. 3.7) | int32 intermediate |
+//            amplitude scaling + eps flip + store / accumulate / SGD update (Def. 3.8, Sec. 4)
+//
+// Index-bit choreography for a tile (b0..b14 = bits of the tile-local coordinate):
+//   L0 (global loads, 16 B per lane): regs = (b0,b1,b8,b9,b10,b11) lanes = (b2..b7)   waves = (b12,b13,b14)
+//   L1 (after the intra-wave exchange): regs = (b2..b7)            lanes = (b0,b1,b8,b9,b10,b11)
+//   L2 (after the cross-wave exchange): regs = (b6,b7,b8,b12,b13,b14) lanes = (b0..b5) waves = (b9,b10,b11)
+// In L2 a wave holds 64 consecutive coordinates per register, so one compare per register yields
+// a packed 64-bit word, and the four registers that differ in (b6,b7) share one dither draw.
+#pragma once
+#include "fo_device.h"
+
+namespace fo {
+
+enum { IN_GRAD = 0, IN_F32 = 1, IN_BITS = 2 };
+enum { OUT_PACK = 0, OUT_I32 = 1, OUT_F32 = 2 };
+enum { STORE_SET = 0, STORE_ACC = 1, STORE_AXPY = 2 };
+
+struct PtrTab {
+    const float *p[64];
+};
+
+struct ContigArgs {
+    const void *src;        // IN_F32: fp32 [slot][ntot]; IN_BITS: uint64 [slot][W]; IN_GRAD: unused if use_tab
+    uint64_t src_stride;    // elements between party slots
+    void *dst;              // OUT_PACK: uint64 [slot][W]; OUT_I32: int32 [slot][ntot]; OUT_F32: fp32 [len_out]
+    uint64_t dst_stride;
+    float *scales;          // [slot][nblocks]
+    uint64_t scales_stride;
+    uint64_t len_in;        // valid input coordinates (IN_GRAD)
+    uint64_t len_out;       // valid output coordinates (OUT_F32)
+    uint64_t W;             // packed words per party
+    uint64_t nblocks;
+    uint32_t S;             // stages inside the tile = min(log2 b, 15)
+    uint32_t logb;          // log2 of the transform length
+    uint32_t use_tab;       // IN_GRAD: take the source pointer of slot y from the pointer table
+    uint32_t compute_scale; // IN_GRAD: derive lambda from the measured block norm (else read scales[])
+    uint32_t dither;        // 0 uniform, 1 none
+    uint32_t store_mode;    // OUT_F32: STORE_*
+    uint32_t party0;        // party id of slot 0 (slot y is party0 + y); FO_PARTY_SERVER stays as is
+    uint32_t eps_party0;    // same for the eps stream
+    uint32_t k0, k1, round_lo;
+    float coef_lambda;      // alpha * sqrt(ln b / b)
+    float sqrtb;            // threshold in the unnormalised domain = lambda * sqrt(b)
+    float out_coef;         // OUT_F32: value = lambda * out_coef * (H^T q)_i  (1/sqrt(b), times 1/M on the server)
+    float delta;            // STORE_AXPY: x -= delta * value
+};
+
+template <int IN, int OUT>
+__global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
+{
+    using T = typename std::conditional<IN == IN_BITS, int32_t, float>::type;
+    __shared__ uint32_t lds[kLdsWords];
+    uint32_t *const xbuf = lds;
+    uint32_t *const epsw = lds + kXWords;
+    float *const lam = reinterpret_cast<float *>(lds + kXWords + kEpsWords);
+    float *const red = reinterpret_cast<float *>(lds + kXWords + kEpsWords + kLamWords);
+
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
+    const uint64_t base = (uint64_t)tile << kTileLog2;
+    const uint32_t S = a.S;
+    const uint32_t party = (a.party0 == 0xFFFFFFFFu) ? a.party0 : a.party0 + slot;
+    const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
+    const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
+    const RngKey key_dit = { a.k0, a.k1, kDomainDither, a.round_lo, party };
+
+    T v[kV];
+
+    // ------------------------------------------------------------------ input, layout L0
+    if constexpr (IN == IN_GRAD || IN == IN_F32) {
+        const float *src = (IN == IN_GRAD && a.use_tab) ? tab.p[slot]
+                                                        : static_cast<const float *>(a.src) + slot * a.src_stride;
+        const uint64_t limit = (IN == IN_GRAD) ? a.len_in : ~0ull;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const uint64_t i = base + wave * 4096u + c * 256u + lane * 4u;
+            float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i + 3 < limit) {
+                x = *reinterpret_cast<const float4 *>(src + i);
+            } else {
+                if (i < limit) x.x = src[i];
+                if (i + 1 < limit) x.y = src[i + 1];
+                if (i + 2 < limit) x.z = src[i + 2];
+            }
+            v[4 * c + 0] = x.x; v[4 * c + 1] = x.y; v[4 * c + 2] = x.z; v[4 * c + 3] = x.w;
+        }
+    } else {
+        const uint64_t *src = static_cast<const uint64_t *>(a.src) + slot * a.src_stride;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const uint64_t gw = (uint64_t)tile * 512u + wave * 64u + c * 4u + (lane >> 4);
+            const uint64_t w = (gw < a.W) ? src[gw] : 0ull;
+            const uint32_t nib = (uint32_t)(w >> ((lane & 15u) * 4u));
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[4 * c + k] = (int32_t)(((nib >> k) & 1u) << 1) - 1;
+        }
+    }
+
+    if constexpr (IN == IN_GRAD) {
+        // per-block sum of squares of the raw gradient (sign flips do not change it)
+        if (a.compute_scale) {
+            const uint32_t G = S < 12u ? S : 12u;        // segment = 2^G coordinates, inside one wave and one block
+            const uint32_t segs_per_wave = 4096u >> G;
+            float acc = 0.f;
+            if (S >= 8u) {
+                const uint32_t cps = 1u << (G - 8u);      // chunks per segment
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    acc += (v[4 * c] * v[4 * c] + v[4 * c + 1] * v[4 * c + 1]) +
+                           (v[4 * c + 2] * v[4 * c + 2] + v[4 * c + 3] * v[4 * c + 3]);
+                    if (((c + 1) & (cps - 1u)) == 0u) {
+                        const float s = wave_sum(acc, 6);
+                        if (lane == 0) red[wave * segs_per_wave + ((uint32_t)c >> (G - 8u))] = s;
+                        acc = 0.f;
+                    }
+                }
+            } else {
+                const uint32_t lanes_log2 = S - 2u;       // lanes per segment: 16 or 32
+#pragma unroll
+                for (int c = 0; c < 16; ++c) {
+                    const float p = (v[4 * c] * v[4 * c] + v[4 * c + 1] * v[4 * c + 1]) +
+                                    (v[4 * c + 2] * v[4 * c + 2] + v[4 * c + 3] * v[4 * c + 3]);
+                    const float s = wave_sum(p, (int)lanes_log2);
+                    if ((lane & ((1u << lanes_log2) - 1u)) == 0u)
+                        red[wave * segs_per_wave + c * (256u >> S) + (lane >> lanes_log2)] = s;
+                }
+            }
+        }
+        // eps flip: lanes 0..31 of each wave draw the 32 generator blocks covering the wave's 4096 coordinates
+        if (lane < 32u) {
+            uint32_t w[4];
+            philox((uint32_t)((base + wave * 4096u) >> 7) + lane, key_eps, w);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) epsw[wave * 128u + lane * 4u + j] = w[j];
+        }
+        wave_sync();
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            const uint32_t nib = epsw[wave * 128u + c * 8u + (lane >> 3)] >> ((lane & 7u) * 4u);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[4 * c + k] = flip_if(v[4 * c + k], (nib >> k) & 1u);
+        }
+    }
+
+    // ------------------------------------------------------------------ round 1: b0,b1,b8..b11
+    bfly<T, 0>(v);
+    bfly<T, 1>(v);
+    if (S > 8u) bfly<T, 2>(v);
+    if (S > 9u) bfly<T, 3>(v);
+    if (S > 10u) bfly<T, 4>(v);
+    if (S > 11u) bfly<T, 5>(v);
+
+    // ------------------------------------------------------------------ exchange L0 -> L1 (inside each wave)
+    {
+        uint32_t *const wb = xbuf + wave * 2112u + (lane >> 5) * 1056u;
+        const uint32_t col = lane & 31u;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+#pragma unroll
+            for (int r = 0; r < 32; ++r) wb[r * 33 + col] = __builtin_bit_cast(uint32_t, v[sub * 32 + r]);
+            wave_sync();
+#pragma unroll
+            for (int r = 0; r < 32; ++r) v[sub * 32 + r] = __builtin_bit_cast(T, wb[col * 33 + r]);
+            wave_sync();
+        }
+        swap_reg5_lane5(v);
+    }
+
+    // ------------------------------------------------------------------ round 2: b2..b7
+    bfly<T, 0>(v);
+    bfly<T, 1>(v);
+    bfly<T, 2>(v);
+    bfly<T, 3>(v);
+    if (S > 6u) bfly<T, 4>(v);
+    if (S > 7u) bfly<T, 5>(v);
+
+    __syncthreads();
+
+    // ------------------------------------------------------------------ amplitudes of the tile's blocks
+    const uint32_t nblk_tile = kTile >> S;
+    const uint64_t blk0 = (a.logb <= (uint32_t)kTileLog2) ? (uint64_t)tile * nblk_tile : (base >> a.logb);
+    if constexpr (OUT != OUT_I32) {
+        if (t < nblk_tile) {
+            float l = 0.f;
+            const uint64_t gb = blk0 + t;
+            if (IN == IN_GRAD && a.compute_scale) {
+                float s;
+                if (S <= 12u) {
+                    s = red[t];
+                } else {
+                    const uint32_t per = 1u << (S - 12u);
+                    s = 0.f;
+                    for (uint32_t k = 0; k < per; ++k) s += red[t * per + k];
+                }
+                l = a.coef_lambda * sqrtf(s);
+                if (gb < a.nblocks) a.scales[slot * a.scales_stride + gb] = l;
+            } else if (gb < a.nblocks) {
+                l = a.scales[slot * a.scales_stride + gb];
+            }
+            lam[t] = l;
+        }
+    }
+    if constexpr (OUT == OUT_F32) {
+        // eps words for layout L2: lane q < 32 of wave w draws the block that covers (b7,b8,b12..b14) = q, (b9..b11) = w
+        if (lane < 32u) {
+            uint32_t w[4];
+            const uint32_t call = (lane & 3u) | (wave << 2) | ((lane >> 2) << 5);
+            philox((uint32_t)(base >> 7) + call, key_eps, w);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) epsw[wave * 128u + lane * 4u + j] = w[j];
+        }
+    }
+
+    // ------------------------------------------------------------------ exchange L1 -> L2 (whole workgroup)
+    {
+        const uint32_t wofs = (lane & 3u) + ((lane >> 2) | (wave << 4)) * 132u;
+        const uint32_t rofs = lane + wave * 264u;
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+            if (sub) __syncthreads();
+#pragma unroll
+            for (int r = 0; r < 32; ++r) xbuf[wofs + r * 4] = __builtin_bit_cast(uint32_t, v[sub * 32 + r]);
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < kV; ++r)
+                if (((r >> 1) & 1) == sub)
+                    v[r] = __builtin_bit_cast(T, xbuf[rofs + (r & 1) * 64 + (((r >> 2) & 1) + (r >> 3) * 16) * 132]);
+        }
+    }
+
+    // ------------------------------------------------------------------ round 3: b12,b13,b14
+    if (S > 12u) bfly<T, 3>(v);
+    if (S > 13u) bfly<T, 4>(v);
+    if (S > 14u) bfly<T, 5>(v);
+
+    // tile-local coordinate of register r in L2: lane | b6<<6 | b7<<7 | b8<<8 | wave<<9 | (r>>3)<<12
+    auto local_of = [&](int r) -> uint32_t {
+        return lane | ((uint32_t)(r & 7) << 6) | (wave << 9) | ((uint32_t)(r >> 3) << 12);
+    };
+
+    // ------------------------------------------------------------------ output
+    if constexpr (OUT == OUT_PACK) {
+        uint32_t my_lo = 0u, my_hi = 0u;
+        const float tscale = a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m * 2^-24 with m odd
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            uint32_t w[4] = { 0u, 0u, 0u, 0u };
+            const uint32_t lg = local_of(4 * g); // b6 = b7 = 0
+            if (a.dither == 0u) philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_dit, w);
+            float thr_g = 0.f;
+            if (S >= 8u) thr_g = lam[lg >> S] * tscale;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int r = 4 * g + s;
+                float thr = thr_g;
+                if (S < 8u) thr = lam[local_of(r) >> S] * tscale;
+                float tv = v[r];
+                if (a.dither == 0u) {
+                    const int32_t m = (int32_t)((w[s] >> 8) << 1) - 16777215; // 2 r + 1 - 2^24
+                    tv = fmaf(thr, (float)m, tv);
+                }
+                const uint64_t word = __ballot(tv >= 0.f);
+                if (lane == (uint32_t)r) {
+                    my_lo = (uint32_t)word;
+                    my_hi = (uint32_t)(word >> 32);
+                }
+            }
+        }
+        // lane j holds the word of register j
+        const uint64_t gw = (uint64_t)tile * 512u + ((lane & 7u) | (wave << 3) | ((lane >> 3) << 6));
+        if (gw < a.W)
+            static_cast<uint64_t *>(a.dst)[slot * a.dst_stride + gw] = ((uint64_t)my_hi << 32) | my_lo;
+    } else if constexpr (OUT == OUT_I32) {
+        int32_t *dst = static_cast<int32_t *>(a.dst) + slot * a.dst_stride + base;
+#pragma unroll
+        for (int r = 0; r < kV; ++r) dst[local_of(r)] = v[r];
+    } else {
+        float *dst = static_cast<float *>(a.dst);
+#pragma unroll
+        for (int r = 0; r < kV; ++r) {
+            const uint32_t loc = local_of(r);
+            const uint64_t i = base + loc;
+            const uint32_t ew = epsw[wave * 128u + (r >> 1) * 4 + ((r & 1) << 1) + (lane >> 5)];
+            const float val = flip_if((lam[loc >> S] * a.out_coef) * (float)v[r], (ew >> (lane & 31u)) & 1u);
+            if (i < a.len_out) {
+                if (a.store_mode == STORE_SET) dst[i] = val;
+                else if (a.store_mode == STORE_ACC) dst[i] += val;
+                else dst[i] -= a.delta * val;
+            }
+        }
+    }
+}
+
+} // namespace fo

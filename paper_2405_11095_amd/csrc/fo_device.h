@@ -1,0 +1,111 @@
+// Device-side building blocks of the FO-SGD codec kernels (gfx950, wave64).
+//
+// Tile model.  Every kernel works on tiles of 2^15 coordinates held entirely in the registers
+// of one 512-thread workgroup: 64 values per thread.  A Walsh-Hadamard stage on index bit k is
+// a butterfly between two registers of one thread whenever bit k is mapped to the register
+// number; the kernels therefore alternate "register rounds" (six stages each, no data
+// movement) with exchanges through LDS that remap which index bits live in registers.
+// Stages commute, so each kernel visits the bits in the order that suits its memory layout.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fo {
+
+constexpr int kTileLog2 = 15;
+constexpr uint32_t kTile = 1u << kTileLog2;
+constexpr int kThreads = 512;
+constexpr int kV = 64;             // values per thread
+constexpr uint32_t kXWords = 16896; // exchange buffer: 128 rows of 128 words padded to 132
+constexpr uint32_t kEpsWords = 1024;
+constexpr uint32_t kLamWords = 512;
+constexpr uint32_t kRedWords = 520;
+constexpr uint32_t kLdsWords = kXWords + kEpsWords + kLamWords + kRedWords;
+
+constexpr uint32_t kDomainEps = 1u;
+constexpr uint32_t kDomainDither = 2u;
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): ten rounds of two 32x32->64 multiplies whose high
+// halves are mixed with the neighbouring words and the round key; the key advances by two Weyl
+// increments per round.  The key schedule is wave-uniform and lives in scalar registers.
+// ---------------------------------------------------------------------------------------------
+struct RngKey {
+    uint32_t k0, k1; // key: seed low word, seed high word xor round high word
+    uint32_t c1;     // domain | k << 8
+    uint32_t c2;     // round low word
+    uint32_t c3;     // party
+};
+
+__device__ __forceinline__ void philox(uint32_t counter, const RngKey &key, uint32_t (&out)[4])
+{
+    uint32_t x0 = counter, x1 = key.c1, x2 = key.c2, x3 = key.c3;
+    uint32_t ka = key.k0, kb = key.k1;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t lo_a = x0 * 0xD2511F53u, hi_a = __umulhi(x0, 0xD2511F53u);
+        const uint32_t lo_b = x2 * 0xCD9E8D57u, hi_b = __umulhi(x2, 0xCD9E8D57u);
+        x0 = hi_b ^ x1 ^ ka;
+        x2 = hi_a ^ x3 ^ kb;
+        x1 = lo_b;
+        x3 = lo_a;
+        ka += 0x9E3779B9u;
+        kb += 0xBB67AE85u;
+    }
+    out[0] = x0; out[1] = x1; out[2] = x2; out[3] = x3;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void wave_sync()
+{
+    // Orders LDS traffic between lanes of one wave: the LDS queue of a wave is in order, the
+    // fences keep the compiler from moving accesses across this point.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ float flip_if(float x, uint32_t bit) // bit in {0,1}
+{
+    return __uint_as_float(__float_as_uint(x) ^ (bit << 31));
+}
+
+template <typename T, int BIT>
+__device__ __forceinline__ void bfly(T (&v)[kV])
+{
+#pragma unroll
+    for (int r = 0; r < kV; ++r)
+        if (!(r & (1 << BIT))) {
+            const T a = v[r], b = v[r | (1 << BIT)];
+            v[r] = a + b;
+            v[r | (1 << BIT)] = a - b;
+        }
+}
+
+__device__ __forceinline__ float wave_sum(float s, int steps) // butterfly sum over 2^steps lanes
+{
+#pragma unroll
+    for (int k = 0; k < 6; ++k)
+        if (k < steps) s += __shfl_xor(s, 1 << k, 64);
+    return s;
+}
+
+// Swap register bit 5 with lane bit 5: afterwards v[k] of the upper half-wave and v[k+32] of
+// the lower half-wave have traded places.
+template <typename T>
+__device__ __forceinline__ void swap_reg5_lane5(T (&v)[kV])
+{
+#pragma unroll
+    for (int k = 0; k < 32; ++k) {
+        const uint32_t lo = __builtin_bit_cast(uint32_t, v[k]);
+        const uint32_t hi = __builtin_bit_cast(uint32_t, v[k + 32]);
+        // v_permlane32_swap: lanes 32..63 of the first operand trade with lanes 0..31 of the second
+        const auto r = __builtin_amdgcn_permlane32_swap(lo, hi, false, false);
+        v[k] = __builtin_bit_cast(T, (uint32_t)r[0]);
+        v[k + 32] = __builtin_bit_cast(T, (uint32_t)r[1]);
+    }
+}
+
+} // namespace fo

@@ -1,0 +1,146 @@
+"""Staged parity harness: the HIP codec against the CPU oracle on the same seeded inputs.
+
+Stages are teacher-forced: each stage's oracle is fed the GPU's own upstream output (uplink bits
+and fp32 amplitudes), because one legitimately exempt near-tie flip upstream would otherwise move
+every downstream value.  Gates (from the paper's arithmetic and the build's target):
+  - packed sign bits equal the oracle's except at coordinates whose pre-quantisation value
+    |z_i + tau_i| is below 1e-6 * lambda (counted and reported);
+  - amplitudes within 1e-6 relative of the oracle's own rule;
+  - mean gradient, decoded vector and updated iterate within 1e-5 relative l2.
+"""
+from __future__ import annotations
+
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+TIE = 1e-6
+SERVER = 0xFFFFFFFF
+
+
+def rel_l2(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a - b))
+
+
+def bits_to_bool(bits, n):
+    return np.unpackbits(np.ascontiguousarray(bits).view(np.uint8), bitorder="little")[:n].astype(bool)
+
+
+def compare_bits(gpu_bits, margin, lam, b):
+    """(mismatches outside the near-tie exemption, exempt coordinates, raw mismatches)."""
+    n = margin.size
+    want = margin >= 0.0
+    got = bits_to_bool(gpu_bits, n)
+    lam_c = np.repeat(np.asarray(lam, dtype=np.float64), b)[:n]
+    exempt = np.abs(margin) < TIE * lam_c
+    diff = want != got
+    return int(np.count_nonzero(diff & ~exempt)), int(np.count_nonzero(exempt)), int(np.count_nonzero(diff))
+
+
+def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha=2.0, alpha_s=2.0,
+                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True):
+    """Runs encode x M, server, decode and fo_step on the GPU and compares every stage with the
+    oracle.  Returns a report dict; asserts nothing (callers apply the gates)."""
+    import torch
+
+    plan = B.Plan(d=d, M=M, block_log2=block_log2, dither=dither, scale_rule=scale_rule, alpha=alpha,
+                  alpha_s=alpha_s, B=Bnorm, seed=seed)
+    p = O.params(d=d, M=M, block_log2=block_log2, dither=dither, scale_rule=scale_rule, alpha=alpha,
+                 alpha_s=alpha_s, B=Bnorm, seed=seed)
+    b, nb, nt = O.geometry(p)
+    assert (plan.b, plan.nblocks, plan.ntot) == (b, nb, nt)
+    W = nt // 64
+    gd = [torch.from_numpy(g).to(device) for g in gs]
+    bits_up = torch.zeros((M, W), dtype=torch.int64, device=device)
+    lam_up = torch.zeros((M, nb), dtype=torch.float32, device=device)
+    for m in range(M):
+        plan.fo_encode(gd[m], rnd, m, bits_up[m], lam_up[m])
+    bits_down = torch.zeros(W, dtype=torch.int64, device=device)
+    lam_s = torch.zeros(nb, dtype=torch.float32, device=device)
+    gbar = torch.zeros(nt, dtype=torch.float32, device=device)
+    plan.fo_server_aggregate(bits_up, lam_up, rnd, bits_down, lam_s, gbar)
+    out = torch.zeros(d, dtype=torch.float32, device=device)
+    plan.fo_decode(bits_down, lam_s, rnd, SERVER, out)
+    torch.cuda.synchronize()
+    h_bits_up = bits_up.cpu().numpy().view(np.uint64)
+    h_lam_up = lam_up.cpu().numpy()
+    h_bits_down = bits_down.cpu().numpy().view(np.uint64)
+    h_lam_s = lam_s.cpu().numpy()
+    h_gbar = gbar.cpu().numpy()
+    h_out = out.cpu().numpy()
+
+    rep = dict(d=d, M=M, b=b, nblocks=nb)
+
+    # ---- stage (i): uplink, oracle forced to the GPU's fp32 amplitudes
+    def uplink(m):
+        x = gs[m].astype(np.float64)
+        free = O.encode(p, x, rnd, m)["lam"]
+        r = O.encode(p, x, rnd, m, lam=h_lam_up[m].astype(np.float64), want_margin=True)
+        bad, exempt, raw = compare_bits(h_bits_up[m], r["margin"], h_lam_up[m], b)
+        den = np.where(free > 0, free, 1.0)
+        lam_err = float(np.max(np.abs(h_lam_up[m] - free) / den))
+        return bad, exempt, raw, lam_err
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        res = list(ex.map(uplink, range(M)))
+    rep["uplink_mismatch"] = sum(r[0] for r in res)
+    rep["uplink_exempt"] = sum(r[1] for r in res)
+    rep["uplink_raw_diff"] = sum(r[2] for r in res)
+    rep["lam_rel_err"] = max(r[3] for r in res)
+
+    # ---- stage (ii): server, oracle fed the GPU's uplink messages and the GPU's lambda^s
+    free_s = O.server_lambda(p, h_lam_up.astype(np.float64))
+    den = np.where(free_s > 0, free_s, 1.0)
+    rep["lam_s_rel_err"] = float(np.max(np.abs(h_lam_s - free_s) / den))
+    s = O.server(p, h_bits_up, h_lam_up.astype(np.float64), rnd, lam_s=h_lam_s.astype(np.float64), want_margin=True)
+    rep["gbar_rel_l2"] = rel_l2(h_gbar, s["gbar"])
+    bad, exempt, raw = compare_bits(h_bits_down, s["margin"], h_lam_s, b)
+    rep["downlink_mismatch"], rep["downlink_exempt"], rep["downlink_raw_diff"] = bad, exempt, raw
+
+    # ---- stage (iii): worker decode of the GPU's downlink message
+    dec = O.decode(p, O.unpack(h_bits_down, nt), h_lam_s.astype(np.float64), rnd, SERVER)[:d]
+    rep["decode_rel_l2"] = rel_l2(h_out, dec)
+
+    # ---- fo_step: same messages as the calls made by hand, and the SGD update
+    if check_step:
+        x0 = np.random.default_rng(12345).standard_normal(d).astype(np.float32)
+        x = torch.from_numpy(x0.copy()).to(device)
+        plan.fo_step(gd, x, delta, rnd)
+        torch.cuda.synchronize()
+        pb_up, ps_up, pb_dn, ps_dn = plan.fo_step_messages()
+        step_bits_up = _peek(torch, pb_up, M * W, torch.int64, device).view(np.uint64).reshape(M, W)
+        step_lam_up = _peek(torch, ps_up, M * nb, torch.float32, device).reshape(M, nb)
+        step_bits_dn = _peek(torch, pb_dn, W, torch.int64, device).view(np.uint64)
+        step_lam_s = _peek(torch, ps_dn, nb, torch.float32, device)
+        rep["step_messages_equal"] = bool(
+            np.array_equal(step_bits_up, h_bits_up) and np.array_equal(step_lam_up, h_lam_up)
+            and np.array_equal(step_bits_dn, h_bits_down) and np.array_equal(step_lam_s, h_lam_s))
+        want_x = x0.astype(np.float64) - delta * dec
+        rep["x_rel_l2"] = rel_l2(x.cpu().numpy().astype(np.float64) - x0, want_x - x0)
+    plan.close()
+    return rep
+
+
+def _peek(torch, addr, count, dtype, device):
+    """Copy `count` elements at device address `addr` (plan scratch) to a NumPy array."""
+    import ctypes as C
+    itemsize = torch.empty(0, dtype=dtype).element_size()
+    dst = torch.empty(count, dtype=dtype, device=device)
+    hip = C.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int]
+    rc = hip.hipMemcpy(dst.data_ptr(), addr, count * itemsize, 3)  # device to device
+    assert rc == 0
+    return dst.cpu().numpy()
+
+
+def gates(rep, tol=1e-5):
+    assert rep["uplink_mismatch"] == 0, rep
+    assert rep["downlink_mismatch"] == 0, rep
+    assert rep["lam_rel_err"] <= 1e-6 and rep["lam_s_rel_err"] <= 1e-6, rep
+    assert rep["gbar_rel_l2"] <= tol and rep["decode_rel_l2"] <= tol, rep
+    if "x_rel_l2" in rep:
+        assert rep["step_messages_equal"], rep
+        assert rep["x_rel_l2"] <= tol, rep

@@ -432,3 +432,17 @@ def test_stream_layout_matches_the_stated_mapping(oracle):
             w = oracle.rng(seed, oracle.DOMAIN_DITHER, rnd, party, k, ((i >> 8) << 6) | (i & 63))
             r = int(w[(i >> 6) & 3]) >> 8
             assert oracle.dither_u(seed, rnd, party, k, [i])[0] == (2 * r + 1 - 2 ** 24) / 2 ** 24
+
+
+def test_block_range_equals_full(oracle):
+    """Encoding / decoding a range of blocks alone gives the same result as the whole vector."""
+    d = 1000                                 # 16 blocks of 64 -> 1024
+    p = oracle.params(d=d, seed=3, block_log2=6)
+    x = np.random.default_rng(4).standard_normal(d)
+    full = oracle.encode(p, x, 2, 1, want_margin=True)
+    part = oracle.encode_blocks(p, x[64 * 13:], 2, 1, j0=13, nj=3, want_margin=True)
+    assert np.array_equal(part["q"], full["q"][64 * 13:]) and np.array_equal(part["lam"], full["lam"][13:])
+    assert np.array_equal(part["margin"], full["margin"][64 * 13:]) and np.array_equal(part["bits"], full["bits"][13:])
+    dec = oracle.decode(p, full["q"], full["lam"], 2, 1)
+    decp = oracle.decode_blocks(p, full["q"][64 * 5:64 * 9], full["lam"][5:9], 2, 1, j0=5, nj=4)
+    assert np.array_equal(decp, dec[64 * 5:64 * 9])
