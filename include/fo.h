@@ -10,8 +10,9 @@
  *
  * Conventions common to all calls
  *   - Every pointer named "device" is a device (HBM) pointer owned by the caller.  The library
- *     never frees or keeps them beyond the call's enqueued work.  float / uint64 device buffers
- *     must be 16-byte aligned (FO_EALIGN otherwise).  Host pointers are said to be host.
+ *     never frees or keeps them beyond the call's enqueued work.  Alignment (FO_EALIGN otherwise):
+ *     gradients g and gbar 16 bytes, packed words 8 bytes, scales / out / x 4 bytes.  Host
+ *     pointers are said to be host.
  *   - All work is enqueued on the caller's HIP stream (a hipStream_t passed as void*; NULL is the
  *     default stream).  The hot calls (fo_encode, fo_decode, fo_server_aggregate, fo_step) do
  *     not allocate, do not synchronise with the host and copy nothing between host and device;
@@ -51,7 +52,7 @@ extern "C" {
 
 #define FO_OK 0
 #define FO_EINVAL (-1) /* NULL / out-of-range argument, unsupported parameter value */
-#define FO_EALIGN (-2) /* a device pointer is not 16-byte aligned                      */
+#define FO_EALIGN (-2) /* a device pointer is not aligned as required                      */
 #define FO_EHIP (-3)   /* a HIP runtime call failed; see fo_last_hip_error              */
 #define FO_ENOMEM (-4) /* plan creation could not allocate its scratch memory         */
 

@@ -67,7 +67,7 @@ __global__ void k_server_scales(const float *scales_up, uint64_t nblocks, uint32
     scales_down[j] = nan ? __builtin_nanf("") : coef_s * m;
 }
 
-bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 } // namespace
 
@@ -401,7 +401,7 @@ extern "C" int fo_encode(fo_plan *pl, const float *g, uint64_t round, uint32_t p
     if (!pl || !g || !bits || !scales) return FO_EINVAL;
     if (party != FO_PARTY_SERVER && party >= pl->p.M) return FO_EINVAL;
     if (flags & ~FO_FORCE_SCALE) return FO_EINVAL;
-    if (!aligned16(g) || !aligned16(bits) || !aligned16(scales)) return FO_EALIGN;
+    if (!aligned(g, 16) || !aligned(bits, 8) || !aligned(scales, 4)) return FO_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     bool given;
     int rc = prepare_scales(pl, 1, (flags & FO_FORCE_SCALE) != 0, scales, 0, st, &given);
@@ -415,7 +415,7 @@ extern "C" int fo_decode(fo_plan *pl, const uint64_t *bits, const float *scales,
 {
     if (!pl || !bits || !scales || !out) return FO_EINVAL;
     if (party != FO_PARTY_SERVER && party >= pl->p.M) return FO_EINVAL;
-    if (!aligned16(bits) || !aligned16(scales) || !aligned16(out)) return FO_EALIGN;
+    if (!aligned(bits, 8) || !aligned(scales, 4) || !aligned(out, 4)) return FO_EALIGN;
     return launch_decode(pl, bits, scales, round, party, out, pl->p.d, STORE_SET, pl->rsqrtb, 0.f, pl->buf_a,
                          static_cast<hipStream_t>(hip_stream));
 }
@@ -424,8 +424,8 @@ extern "C" int fo_server_aggregate(fo_plan *pl, const uint64_t *bits_up, const f
                                    uint64_t *bits_down, float *scales_down, float *gbar_or_null, void *hip_stream)
 {
     if (!pl || !bits_up || !scales_up || !bits_down || !scales_down) return FO_EINVAL;
-    if (!aligned16(bits_up) || !aligned16(scales_up) || !aligned16(bits_down) || !aligned16(scales_down) ||
-        !aligned16(gbar_or_null))
+    if (!aligned(bits_up, 8) || !aligned(scales_up, 4) || !aligned(bits_down, 8) || !aligned(scales_down, 4) ||
+        !aligned(gbar_or_null, 16))
         return FO_EALIGN;
     return launch_server(pl, bits_up, scales_up, round, bits_down, scales_down, gbar_or_null,
                          static_cast<hipStream_t>(hip_stream));
@@ -434,12 +434,12 @@ extern "C" int fo_server_aggregate(fo_plan *pl, const uint64_t *bits_up, const f
 extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta, uint64_t round, void *hip_stream)
 {
     if (!pl || !g || !x) return FO_EINVAL;
-    if (!aligned16(x)) return FO_EALIGN;
+    if (!aligned(x, 4)) return FO_EALIGN;
     PtrTab tab;
     std::memset(&tab, 0, sizeof(tab));
     for (uint32_t m = 0; m < pl->p.M; ++m) {
         if (!g[m]) return FO_EINVAL;
-        if (!aligned16(g[m])) return FO_EALIGN;
+        if (!aligned(g[m], 16)) return FO_EALIGN;
         tab.p[m] = g[m];
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);

@@ -8,9 +8,10 @@
 // Index-bit choreography for a tile (b0..b14 = bits of the tile-local coordinate):
 //   L0 (global loads, 16 B per lane): regs = (b0,b1,b8,b9,b10,b11) lanes = (b2..b7)   waves = (b12,b13,b14)
 //   L1 (after the intra-wave exchange): regs = (b2..b7)            lanes = (b0,b1,b8,b9,b10,b11)
-//   L2 (after the cross-wave exchange): regs = (b6,b7,b8,b12,b13,b14) lanes = (b0..b5) waves = (b9,b10,b11)
+//   L2 (after the cross-wave exchange): regs = (b6,b8,b12,b13,b14,b7) lanes = (b0..b5) waves = (b9,b10,b11)
 // In L2 a wave holds 64 consecutive coordinates per register, so one compare per register yields
 // a packed 64-bit word, and the four registers that differ in (b6,b7) share one dither draw.
+// b7 keeps register bit 5 across the second exchange, so each half of it can run in place.
 #pragma once
 #include "fo_device.h"
 
@@ -206,10 +207,11 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
         }
     }
     if constexpr (OUT == OUT_F32) {
-        // eps words for layout L2: lane q < 32 of wave w draws the block that covers (b7,b8,b12..b14) = q, (b9..b11) = w
+        // eps words for layout L2: lane q < 32 of wave w draws the generator block that covers
+        // (b8,b12,b13,b14) = q & 15, b7 = q >> 4, (b9..b11) = w
         if (lane < 32u) {
             uint32_t w[4];
-            const uint32_t call = (lane & 3u) | (wave << 2) | ((lane >> 2) << 5);
+            const uint32_t call = (lane >> 4) | ((lane & 1u) << 1) | (wave << 2) | (((lane >> 1) & 7u) << 5);
             philox((uint32_t)(base >> 7) + call, key_eps, w);
 #pragma unroll
             for (int j = 0; j < 4; ++j) epsw[wave * 128u + lane * 4u + j] = w[j];
@@ -227,20 +229,21 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
             for (int r = 0; r < 32; ++r) xbuf[wofs + r * 4] = __builtin_bit_cast(uint32_t, v[sub * 32 + r]);
             __syncthreads();
 #pragma unroll
-            for (int r = 0; r < kV; ++r)
-                if (((r >> 1) & 1) == sub)
-                    v[r] = __builtin_bit_cast(T, xbuf[rofs + (r & 1) * 64 + (((r >> 2) & 1) + (r >> 3) * 16) * 132]);
+            for (int q = 0; q < 32; ++q) // register sub*32 + q = (b6,b8,b12,b13,b14 | b7 = sub)
+                v[sub * 32 + q] =
+                    __builtin_bit_cast(T, xbuf[rofs + (q & 1) * 64 + (((q >> 1) & 1) + (q >> 2) * 16) * 132]);
         }
     }
 
     // ------------------------------------------------------------------ round 3: b12,b13,b14
-    if (S > 12u) bfly<T, 3>(v);
-    if (S > 13u) bfly<T, 4>(v);
-    if (S > 14u) bfly<T, 5>(v);
+    if (S > 12u) bfly<T, 2>(v);
+    if (S > 13u) bfly<T, 3>(v);
+    if (S > 14u) bfly<T, 4>(v);
 
-    // tile-local coordinate of register r in L2: lane | b6<<6 | b7<<7 | b8<<8 | wave<<9 | (r>>3)<<12
+    // tile-local coordinate of register r in L2
     auto local_of = [&](int r) -> uint32_t {
-        return lane | ((uint32_t)(r & 7) << 6) | (wave << 9) | ((uint32_t)(r >> 3) << 12);
+        return lane | ((uint32_t)(r & 1) << 6) | ((uint32_t)(r >> 5) << 7) | ((uint32_t)((r >> 1) & 1) << 8) | (wave << 9) |
+               ((uint32_t)((r >> 2) & 7) << 12);
     };
 
     // ------------------------------------------------------------------ output
@@ -250,13 +253,13 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
 #pragma unroll
         for (int g = 0; g < 16; ++g) {
             uint32_t w[4] = { 0u, 0u, 0u, 0u };
-            const uint32_t lg = local_of(4 * g); // b6 = b7 = 0
+            const uint32_t lg = local_of(2 * g); // b6 = b7 = 0
             if (a.dither == 0u) philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_dit, w);
             float thr_g = 0.f;
             if (S >= 8u) thr_g = lam[lg >> S] * tscale;
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
-                const int r = 4 * g + s;
+                const int r = 2 * g + (s & 1) + 32 * (s >> 1); // slot s = b6 | b7 << 1
                 float thr = thr_g;
                 if (S < 8u) thr = lam[local_of(r) >> S] * tscale;
                 float tv = v[r];
@@ -272,7 +275,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
             }
         }
         // lane j holds the word of register j
-        const uint64_t gw = (uint64_t)tile * 512u + ((lane & 7u) | (wave << 3) | ((lane >> 3) << 6));
+        const uint64_t gw = (uint64_t)tile * 512u +
+                            ((lane & 1u) | ((lane >> 5) << 1) | (((lane >> 1) & 1u) << 2) | (wave << 3) | (((lane >> 2) & 7u) << 6));
         if (gw < a.W)
             static_cast<uint64_t *>(a.dst)[slot * a.dst_stride + gw] = ((uint64_t)my_hi << 32) | my_lo;
     } else if constexpr (OUT == OUT_I32) {
@@ -285,7 +289,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
         for (int r = 0; r < kV; ++r) {
             const uint32_t loc = local_of(r);
             const uint64_t i = base + loc;
-            const uint32_t ew = epsw[wave * 128u + (r >> 1) * 4 + ((r & 1) << 1) + (lane >> 5)];
+            const uint32_t ew = epsw[wave * 128u + (((r & 31) >> 1) | ((r >> 5) << 4)) * 4 + ((r & 1) << 1) + (lane >> 5)];
             const float val = flip_if((lam[loc >> S] * a.out_coef) * (float)v[r], (ew >> (lane & 31u)) & 1u);
             if (i < a.len_out) {
                 if (a.store_mode == STORE_SET) dst[i] = val;
