@@ -1,0 +1,131 @@
+#!/usr/bin/env python3
+"""Benchmark of the FO-SGD gradient codec (arXiv 2405.11095) on one MI355X.
+
+A step is one whole FO-SGD iteration of the codec (Sec. 4): M uplink encodes, the server's
+decode + average + re-encode, one downlink decode and the SGD update, all inside fo_step with
+the M synthetic gradients already resident in HBM.  The workload is the ResNet-50-sized one:
+d = 25,557,032 fp32 coordinates zero-padded to n = 2^25, M = 16 workers, heavy-tailed entries.
+
+Prints ONE JSON line.  `value` is GB/s of fp32 gradient processed (4 d M bytes per step).
+`roofline` is for the kernel with the largest share of the step, timed with HIP events on the
+launch stream inside the timed region.  `cpu_baseline` is the plain fp64 oracle timed on the host.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/),
+# keyed by kernel name; None until a counter run for that kernel is on file.
+MEASURED_TRAFFIC = {}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the M workers are M buffers on one device); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2405_11095_amd import binding as B, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    wl = inputs.WORKLOADS[args.workload]
+    d, M = wl["d"], wl["M"]
+    t0 = time.time()
+    gs_host = inputs.workload(args.workload)
+    gs = [torch.from_numpy(g).to(dev) for g in gs_host]
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan = B.Plan(d=d, M=M, block_log2=0, seed=0xF05D + 3)
+    n = plan.ntot
+    print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "
+          f"plan scratch {plan.scratch_bytes / 2**30:.2f} GiB", file=sys.stderr, flush=True)
+
+    delta = 1e-3
+    for w in range(args.warmup):
+        plan.fo_step(gs, x, delta, w)
+    torch.cuda.synchronize()
+    plan.fo_profile_begin()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        plan.fo_step(gs, x, delta, args.warmup + k)
+    torch.cuda.synchronize()
+    t_end = time.perf_counter()
+    prof = plan.fo_profile_end()
+    sec = (t_end - t_start) / args.steps
+    value = 4.0 * d * M / sec / 1e9
+
+    # roofline of the dominant kernel
+    per_kernel = {k: (l, ms) for k, (l, ms) in prof.items()}
+    dom = max(per_kernel, key=lambda k: per_kernel[k][1])
+    launches, total_ms = per_kernel[dom]
+    avg_ms = total_ms / launches
+    # kernels launched with two different batch sizes per step have a per-step algorithmic figure
+    W8 = n // 8
+    per_step = {
+        "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
+        "k_contig<IN_F32,OUT_PACK>": (M + 1) * (4 * n + W8),
+        "k_contig<IN_BITS,OUT_I32>": (M + 1) * (W8 + 4 * n),
+        "k_strided<SERVER>": M * 4 * n + 4 * n,
+        "k_strided<DEC_LAST>": 4 * n + 8 * d,
+        "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
+        "k_contig<IN_BITS,OUT_F32>": M * (W8 + 8 * n) + (W8 + 8 * d),
+    }
+    step_bytes = per_step.get(dom)
+    bytes_per_launch = step_bytes * args.steps / launches if step_bytes else None
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if bytes_per_launch else None
+    roofline = {
+        "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None,
+        "traffic": MEASURED_TRAFFIC.get(dom),
+        "avg_launch_ms": round(avg_ms, 4), "bytes_per_launch": bytes_per_launch,
+        "kernel_ms_per_step": {k: round(ms / args.steps, 4) for k, (l, ms) in sorted(per_kernel.items())},
+        "step_model_bytes": sum(v for k, v in per_step.items() if k in per_kernel),
+    }
+    roofline["step_frac_of_hbm_peak"] = round(roofline["step_model_bytes"] / sec / 1e9 / HBM_PEAK_GBS, 4)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import fo_oracle as O
+        Ms = min(8, M)                                   # bounded sample: the first Ms workers, full d
+        nthreads = max(1, min(Ms, 16, os.cpu_count() or 1))
+        p = O.params(d=d, M=Ms, block_log2=0, seed=0xF05D + 3)
+        xo = np.zeros(d, dtype=np.float64)
+        c0 = time.perf_counter()
+        O.round_trip(p, gs_host[:Ms], xo, delta, 0, nthreads=nthreads)
+        c1 = time.perf_counter()
+        cpu = {"value": round(4.0 * d * Ms / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
+               "sample": f"one full round trip of the same workload with the first {Ms} of {M} workers "
+                         f"(d={d}, n={n}), fp64; the {Ms} encodes run one per thread, the server and the "
+                         f"downlink decode on one thread; {c1 - c0:.1f} s"}
+
+    out = {
+        "metric": "GB/s of fp32 gradient encoded+aggregated+decoded; % of HBM roofline",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: d={d} fp32 padded to n={n}, M={M} workers, full-length randomized FWHT, "
+                               f"uniform dither, L2 scale rule, alpha=alpha_s=2, independent eps, one fo_step per step",
+                   "d": d, "n": n, "M": M, "block_log2": 0},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -135,6 +135,19 @@ int fo_step(fo_plan *plan, const float *const *g, float *x, float delta, uint64_
 int fo_step_messages(fo_plan *plan, const uint64_t **bits_up, const float **scales_up,
                      const uint64_t **bits_down, const float **scales_down);
 
+/* Optional per-kernel timing, for benchmarks (not part of the paper's method).  After
+ * fo_profile_begin every kernel the hot calls enqueue on this plan is bracketed by two HIP events
+ * on the caller's stream (the first call creates the events: it allocates, the hot calls still do
+ * not).  fo_profile_end waits for the recorded work, writes one entry per kernel that ran into
+ * the host array out[cap], sets *count and stops recording.  At most 8192 launches are recorded. */
+typedef struct {
+    char name[48];     /* kernel name as it appears in a rocprofv3 kernel trace (template form) */
+    uint32_t launches;
+    float total_ms;    /* sum of the launches' durations                                         */
+} fo_kernel_time;
+int fo_profile_begin(fo_plan *plan);
+int fo_profile_end(fo_plan *plan, fo_kernel_time *out, size_t cap, size_t *count);
+
 #ifdef __cplusplus
 }
 #endif

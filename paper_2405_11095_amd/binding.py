@@ -23,7 +23,7 @@ MAX_WORKERS = 64
 
 EXPORTS = ("fo_plan_create", "fo_plan_destroy", "fo_padded_len", "fo_packed_words", "fo_num_scales",
            "fo_block_len", "fo_scratch_bytes", "fo_last_hip_error", "fo_encode", "fo_decode",
-           "fo_server_aggregate", "fo_step", "fo_step_messages")
+           "fo_server_aggregate", "fo_step", "fo_step_messages", "fo_profile_begin", "fo_profile_end")
 
 
 class FoError(RuntimeError):
@@ -40,6 +40,10 @@ class Params(C.Structure):
     _fields_ = [("d", C.c_uint64), ("M", C.c_uint32), ("block_log2", C.c_uint32), ("K", C.c_uint32),
                 ("dither", C.c_uint32), ("scale_rule", C.c_uint32), ("eps_mode", C.c_uint32),
                 ("alpha", C.c_float), ("alpha_s", C.c_float), ("B", C.c_float), ("seed", C.c_uint64)]
+
+
+class KernelTime(C.Structure):
+    _fields_ = [("name", C.c_char * 48), ("launches", C.c_uint32), ("total_ms", C.c_float)]
 
 
 _lib = None
@@ -66,6 +70,8 @@ def load_library():
         lib.fo_server_aggregate.argtypes = [vp, vp, vp, u64, vp, vp, vp, vp]
         lib.fo_step.argtypes = [vp, C.POINTER(vp), vp, C.c_float, u64, vp]
         lib.fo_step_messages.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+        lib.fo_profile_begin.argtypes = [vp]
+        lib.fo_profile_end.argtypes = [vp, C.POINTER(KernelTime), C.c_size_t, C.POINTER(C.c_size_t)]
         _lib = lib
     return _lib
 
@@ -146,3 +152,17 @@ class Plan:
         if rc:
             raise FoError(rc, "fo_step_messages")
         return a.value, b.value, c.value, d.value
+
+    def fo_profile_begin(self):
+        rc = load_library().fo_profile_begin(self._h)
+        if rc:
+            raise FoError(rc, "fo_profile_begin")
+
+    def fo_profile_end(self):
+        """{kernel name: (launches, total_ms)} for the kernels that ran since fo_profile_begin."""
+        out = (KernelTime * 16)()
+        n = C.c_size_t()
+        rc = load_library().fo_profile_end(self._h, out, 16, C.byref(n))
+        if rc:
+            raise FoError(rc, "fo_profile_end")
+        return {out[i].name.decode(): (out[i].launches, out[i].total_ms) for i in range(n.value)}

@@ -69,6 +69,34 @@ __global__ void k_server_scales(const float *scales_up, uint64_t nblocks, uint32
 
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
+// Kernel identities for the optional per-kernel timing (fo_profile_begin / fo_profile_end).
+enum KernelId {
+    KID_ENC_SINGLE = 0, // k_contig<IN_GRAD,OUT_PACK>
+    KID_ENC_HIGH,       // k_strided<ENC_FIRST>
+    KID_ENC_MID,        // k_strided<MID_F32>
+    KID_ENC_LOW,        // k_contig<IN_F32,OUT_PACK>
+    KID_DEC_SINGLE,     // k_contig<IN_BITS,OUT_F32>
+    KID_DEC_LOW,        // k_contig<IN_BITS,OUT_I32>
+    KID_DEC_MID,        // k_strided<MID_I32>
+    KID_DEC_HIGH,       // k_strided<DEC_LAST>
+    KID_SERVER_HIGH,    // k_strided<SERVER>
+    KID_SCALES,         // k_finalize_scales / k_fill_scales / k_server_scales
+    KID_COUNT
+};
+const char *const kKernelNames[KID_COUNT] = {
+    "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
+    "k_contig<IN_BITS,OUT_F32>",  "k_contig<IN_BITS,OUT_I32>", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
+    "k_strided<SERVER>", "scale kernels",
+};
+
+struct Profiler {
+    bool on = false;
+    static constexpr int kMax = 8192;
+    hipEvent_t *ev = nullptr; // 2 * kMax events
+    int kid[kMax];
+    int used = 0;
+};
+
 } // namespace
 
 // ---------------------------------------------------------------------------------------------
@@ -93,6 +121,7 @@ struct fo_plan {
     float *scales_up;    // [M][nblocks]
     uint64_t *bits_down; // [W]
     float *scales_down;  // [nblocks]
+    Profiler prof;
 };
 
 extern "C" const char *fo_last_hip_error(void) { return g_hip_err; }
@@ -173,6 +202,10 @@ extern "C" void fo_plan_destroy(fo_plan *plan)
 {
     if (!plan) return;
     if (plan->scratch) (void)hipFree(plan->scratch);
+    if (plan->prof.ev) {
+        for (int i = 0; i < 2 * Profiler::kMax; ++i) (void)hipEventDestroy(plan->prof.ev[i]);
+        delete[] plan->prof.ev;
+    }
     delete plan;
 }
 
@@ -195,9 +228,25 @@ Rng rng_of(const fo_plan *pl, uint64_t round)
     return { (uint32_t)pl->p.seed, (uint32_t)(pl->p.seed >> 32) ^ (uint32_t)(round >> 32), (uint32_t)round };
 }
 
-#define FO_LAUNCH_CHECK(what)                                                       \
-    do {                                                                            \
-        if (!hip_ok(hipGetLastError(), what)) return FO_EHIP;                       \
+// Enqueue one kernel; with profiling on, bracket it with two HIP events on the same stream.
+template <typename Kern, typename... Args>
+int launch(fo_plan *pl, int kid, Kern kernel, dim3 grid, dim3 block, hipStream_t st, Args... args)
+{
+    Profiler &pf = pl->prof;
+    const bool rec = pf.on && pf.used < Profiler::kMax;
+    if (rec && !hip_ok(hipEventRecord(pf.ev[2 * pf.used], st), "hipEventRecord")) return FO_EHIP;
+    hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+    if (!hip_ok(hipGetLastError(), kKernelNames[kid])) return FO_EHIP;
+    if (rec) {
+        if (!hip_ok(hipEventRecord(pf.ev[2 * pf.used + 1], st), "hipEventRecord")) return FO_EHIP;
+        pf.kid[pf.used++] = kid;
+    }
+    return FO_OK;
+}
+#define FO_TRY(expr)               \
+    do {                           \
+        const int rc_ = (expr);    \
+        if (rc_) return rc_;       \
     } while (0)
 
 StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
@@ -248,8 +297,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
         c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
         c.len_in = len_in;
         c.compute_scale = scales_given ? 0u : 1u;
-        hipLaunchKernelGGL((k_contig<IN_GRAD, OUT_PACK>), grid, block, 0, st, c, tb);
-        FO_LAUNCH_CHECK("k_contig<IN_GRAD,OUT_PACK>");
+        FO_TRY(launch(pl, KID_ENC_SINGLE, (k_contig<IN_GRAD, OUT_PACK>), grid, block, st, c, tb));
         return FO_OK;
     }
     // transform lengths above 2^15: high stages first (eps flip and norm on load), low stages last
@@ -259,22 +307,18 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     s.dst = (pl->npass == 2) ? pl->buf_c : tmp; s.dst_stride = (pl->npass == 2) ? 0 : tmp_stride;
     s.partials = pl->partials; s.eps_party0 = party0;
     if (pl->npass == 2 && nslots != 1) return FO_EINVAL; // three-pass transforms are encoded one party at a time
-    hipLaunchKernelGGL((k_strided<SM_ENC_FIRST>), grid, block, 0, st, s, tb);
-    FO_LAUNCH_CHECK("k_strided<ENC_FIRST>");
+    FO_TRY(launch(pl, KID_ENC_HIGH, (k_strided<SM_ENC_FIRST>), grid, block, st, s, tb));
     if (pl->npass == 2) {
         StridedArgs s2 = strided_base(pl, r, 0);
         s2.src = pl->buf_c; s2.dst = tmp; s2.src_stride = 0; s2.dst_stride = tmp_stride;
-        hipLaunchKernelGGL((k_strided<SM_MID_F32>), grid, block, 0, st, s2, none);
-        FO_LAUNCH_CHECK("k_strided<MID_F32>");
+        FO_TRY(launch(pl, KID_ENC_MID, (k_strided<SM_MID_F32>), grid, block, st, s2, none));
     }
     if (!scales_given) {
-        hipLaunchKernelGGL(k_finalize_scales, dim3((unsigned)pl->nblocks, nslots), dim3(256), 0, st, pl->partials,
-                           pl->ntiles, (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda, scales, scales_stride);
-        FO_LAUNCH_CHECK("k_finalize_scales");
+        FO_TRY(launch(pl, KID_SCALES, k_finalize_scales, dim3((unsigned)pl->nblocks, nslots), dim3(256), st, pl->partials,
+                           pl->ntiles, (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda, scales, scales_stride));
     }
     c.src = tmp; c.src_stride = tmp_stride;
-    hipLaunchKernelGGL((k_contig<IN_F32, OUT_PACK>), grid, block, 0, st, c, none);
-    FO_LAUNCH_CHECK("k_contig<IN_F32,OUT_PACK>");
+    FO_TRY(launch(pl, KID_ENC_LOW, (k_contig<IN_F32, OUT_PACK>), grid, block, st, c, none));
     return FO_OK;
 }
 
@@ -293,26 +337,22 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     c.party0 = party; c.eps_party0 = party;
     if (pl->npass == 0) {
         c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
-        hipLaunchKernelGGL((k_contig<IN_BITS, OUT_F32>), grid, block, 0, st, c, none);
-        FO_LAUNCH_CHECK("k_contig<IN_BITS,OUT_F32>");
+        FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32>), grid, block, st, c, none));
         return FO_OK;
     }
     c.dst = tmp; c.dst_stride = 0;
-    hipLaunchKernelGGL((k_contig<IN_BITS, OUT_I32>), grid, block, 0, st, c, none);
-    FO_LAUNCH_CHECK("k_contig<IN_BITS,OUT_I32>");
+    FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32>), grid, block, st, c, none));
     const void *cur = tmp;
     if (pl->npass == 2) {
         StridedArgs s1 = strided_base(pl, r, 0);
         s1.src = tmp; s1.dst = pl->buf_c;
-        hipLaunchKernelGGL((k_strided<SM_MID_I32>), grid, block, 0, st, s1, none);
-        FO_LAUNCH_CHECK("k_strided<MID_I32>");
+        FO_TRY(launch(pl, KID_DEC_MID, (k_strided<SM_MID_I32>), grid, block, st, s1, none));
         cur = pl->buf_c;
     }
     StridedArgs s = strided_base(pl, r, pl->npass - 1);
     s.src = cur; s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
     s.scales = scales; s.scales_stride = 0; s.eps_party0 = party;
-    hipLaunchKernelGGL((k_strided<SM_DEC_LAST>), grid, block, 0, st, s, none);
-    FO_LAUNCH_CHECK("k_strided<DEC_LAST>");
+    FO_TRY(launch(pl, KID_DEC_HIGH, (k_strided<SM_DEC_LAST>), grid, block, st, s, none));
     return FO_OK;
 }
 
@@ -323,9 +363,8 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
     const uint32_t M = pl->p.M;
     PtrTab none;
     std::memset(&none, 0, sizeof(none));
-    hipLaunchKernelGGL(k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), 0, st, scales_up,
-                       pl->nblocks, M, pl->coef_s, scales_down);
-    FO_LAUNCH_CHECK("k_server_scales");
+    FO_TRY(launch(pl, KID_SCALES, k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), st, scales_up,
+                       pl->nblocks, M, pl->coef_s, scales_down));
     const float mean_coef = pl->rsqrtb / (float)M;
     if (pl->npass == 0) {
         // decode every worker into the mean (materialised), then encode the mean
@@ -355,8 +394,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         ContigArgs c = contig_base(pl, r);
         c.src = bits_up; c.src_stride = pl->W;
         c.dst = pl->buf_a; c.dst_stride = pl->ntot;
-        hipLaunchKernelGGL((k_contig<IN_BITS, OUT_I32>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), 0, st, c, none);
-        FO_LAUNCH_CHECK("k_contig<IN_BITS,OUT_I32> (server)");
+        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c, none));
     }
     {
         StridedArgs s = strided_base(pl, r, 0);
@@ -365,8 +403,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.scales = scales_up; s.scales_stride = pl->nblocks;
         s.gbar = gbar_or_null;
         s.M = M; s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
-        hipLaunchKernelGGL((k_strided<SM_SERVER>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), 0, st, s, none);
-        FO_LAUNCH_CHECK("k_strided<SERVER>");
+        FO_TRY(launch(pl, KID_SERVER_HIGH, (k_strided<SM_SERVER>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, s, none));
     }
     {
         ContigArgs c = contig_base(pl, r);
@@ -374,8 +411,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         c.dst = bits_down; c.dst_stride = 0;
         c.scales = scales_down; c.scales_stride = 0;
         c.party0 = FO_PARTY_SERVER; c.eps_party0 = FO_PARTY_SERVER;
-        hipLaunchKernelGGL((k_contig<IN_F32, OUT_PACK>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), 0, st, c, none);
-        FO_LAUNCH_CHECK("k_contig<IN_F32,OUT_PACK> (server)");
+        FO_TRY(launch(pl, KID_ENC_LOW, (k_contig<IN_F32, OUT_PACK>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, c, none));
     }
     return FO_OK;
 }
@@ -385,9 +421,8 @@ int prepare_scales(fo_plan *pl, uint32_t nslots, bool forced, float *scales, uin
 {
     *given = forced;
     if (!forced && pl->p.scale_rule == FO_SCALE_BOUND) {
-        hipLaunchKernelGGL(k_fill_scales, dim3((unsigned)((pl->nblocks + 255) / 256), nslots), dim3(256), 0, st, scales,
-                           scales_stride, pl->nblocks, pl->coef_lambda * pl->p.B);
-        FO_LAUNCH_CHECK("k_fill_scales");
+        FO_TRY(launch(pl, KID_SCALES, k_fill_scales, dim3((unsigned)((pl->nblocks + 255) / 256), nslots), dim3(256), st, scales,
+                           scales_stride, pl->nblocks, pl->coef_lambda * pl->p.B));
         *given = true;
     }
     return FO_OK;
@@ -470,5 +505,47 @@ extern "C" int fo_step_messages(fo_plan *pl, const uint64_t **bits_up, const flo
     if (scales_up) *scales_up = pl->scales_up;
     if (bits_down) *bits_down = pl->bits_down;
     if (scales_down) *scales_down = pl->scales_down;
+    return FO_OK;
+}
+
+extern "C" int fo_profile_begin(fo_plan *pl)
+{
+    if (!pl) return FO_EINVAL;
+    Profiler &pf = pl->prof;
+    if (!pf.ev) {
+        pf.ev = new (std::nothrow) hipEvent_t[2 * Profiler::kMax];
+        if (!pf.ev) return FO_ENOMEM;
+        for (int i = 0; i < 2 * Profiler::kMax; ++i)
+            if (!hip_ok(hipEventCreate(&pf.ev[i]), "hipEventCreate")) return FO_EHIP;
+    }
+    pf.used = 0;
+    pf.on = true;
+    return FO_OK;
+}
+
+extern "C" int fo_profile_end(fo_plan *pl, fo_kernel_time *out, size_t cap, size_t *count)
+{
+    if (!pl || !out || !count) return FO_EINVAL;
+    Profiler &pf = pl->prof;
+    if (!pf.on) return FO_EINVAL;
+    pf.on = false;
+    float total[KID_COUNT] = { 0 };
+    uint32_t launches[KID_COUNT] = { 0 };
+    for (int i = 0; i < pf.used; ++i) {
+        if (!hip_ok(hipEventSynchronize(pf.ev[2 * i + 1]), "hipEventSynchronize")) return FO_EHIP;
+        float ms = 0.f;
+        if (!hip_ok(hipEventElapsedTime(&ms, pf.ev[2 * i], pf.ev[2 * i + 1]), "hipEventElapsedTime")) return FO_EHIP;
+        total[pf.kid[i]] += ms;
+        launches[pf.kid[i]] += 1;
+    }
+    size_t n = 0;
+    for (int k = 0; k < KID_COUNT && n < cap; ++k) {
+        if (!launches[k]) continue;
+        std::snprintf(out[n].name, sizeof(out[n].name), "%s", kKernelNames[k]);
+        out[n].launches = launches[k];
+        out[n].total_ms = total[k];
+        ++n;
+    }
+    *count = n;
     return FO_OK;
 }

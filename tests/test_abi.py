@@ -1,0 +1,60 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol include/fo.h declares,
+and rejects bad arguments without touching a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2405_11095_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fo_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"fo_encode", "fo_decode", "fo_server_aggregate", "fo_step", "fo_plan_create"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2405_11095_amd import binding
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_bad_parameters_are_rejected_on_the_host(lib):
+    from paper_2405_11095_amd import binding as B
+
+    def create(**kw):
+        base = dict(d=1000, M=2, block_log2=0, K=1, dither=0, scale_rule=1, eps_mode=0, alpha=2.0, alpha_s=2.0, B=1.0, seed=1)
+        base.update(kw)
+        p = B.Params(*[base[k] for k, _ in B.Params._fields_])
+        h = C.c_void_p()
+        return lib.fo_plan_create(C.byref(p), C.byref(h))
+
+    assert create(d=0) == B.EINVAL
+    assert create(M=0) == B.EINVAL and create(M=65) == B.EINVAL
+    assert create(block_log2=5) == B.EINVAL and create(block_log2=31) == B.EINVAL
+    assert create(K=2) == B.EINVAL
+    assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=1) == B.EINVAL
+    assert create(alpha=1.5) == B.EINVAL and create(alpha_s=float("nan")) == B.EINVAL
+    assert create(scale_rule=0, B=0.0) == B.EINVAL
+    assert create(d=(1 << 30) + 1) == B.EINVAL
+    assert lib.fo_plan_create(None, None) == B.EINVAL
+    # NULL plan in the hot calls
+    assert lib.fo_encode(None, None, 0, 0, 0, None, None, None) == B.EINVAL
+    assert lib.fo_decode(None, None, None, 0, 0, None, None) == B.EINVAL
+    assert lib.fo_server_aggregate(None, None, None, 0, None, None, None, None) == B.EINVAL
+    assert lib.fo_step(None, None, None, 0.0, 0, None) == B.EINVAL
+    assert lib.fo_padded_len(None) == 0
