@@ -249,6 +249,15 @@ int launch(fo_plan *pl, int kid, Kern kernel, dim3 grid, dim3 block, hipStream_t
         if (rc_) return rc_;       \
     } while (0)
 
+// Strided kernels come in a generic form and one compiled for ten stages next to the contiguous tile.
+template <int MODE>
+int launch_strided(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const StridedArgs &s, const PtrTab &tab)
+{
+    if (s.hb == 10 && s.ls == (uint32_t)kTileLog2)
+        return launch(pl, kid, k_strided<MODE, 6, 10>, grid, dim3(SLayout<6>::T), st, s, tab);
+    return launch(pl, kid, k_strided<MODE, 6, 0>, grid, dim3(SLayout<6>::T), st, s, tab);
+}
+
 StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
 {
     StridedArgs s;
@@ -307,11 +316,11 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     s.dst = (pl->npass == 2) ? pl->buf_c : tmp; s.dst_stride = (pl->npass == 2) ? 0 : tmp_stride;
     s.partials = pl->partials; s.eps_party0 = party0;
     if (pl->npass == 2 && nslots != 1) return FO_EINVAL; // three-pass transforms are encoded one party at a time
-    FO_TRY(launch(pl, KID_ENC_HIGH, (k_strided<SM_ENC_FIRST>), grid, block, st, s, tb));
+    FO_TRY(launch_strided<SM_ENC_FIRST>(pl, KID_ENC_HIGH, grid, st, s, tb));
     if (pl->npass == 2) {
         StridedArgs s2 = strided_base(pl, r, 0);
         s2.src = pl->buf_c; s2.dst = tmp; s2.src_stride = 0; s2.dst_stride = tmp_stride;
-        FO_TRY(launch(pl, KID_ENC_MID, (k_strided<SM_MID_F32>), grid, block, st, s2, none));
+        FO_TRY(launch_strided<SM_MID_F32>(pl, KID_ENC_MID, grid, st, s2, none));
     }
     if (!scales_given) {
         FO_TRY(launch(pl, KID_SCALES, k_finalize_scales, dim3((unsigned)pl->nblocks, nslots), dim3(256), st, pl->partials,
@@ -346,13 +355,13 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     if (pl->npass == 2) {
         StridedArgs s1 = strided_base(pl, r, 0);
         s1.src = tmp; s1.dst = pl->buf_c;
-        FO_TRY(launch(pl, KID_DEC_MID, (k_strided<SM_MID_I32>), grid, block, st, s1, none));
+        FO_TRY(launch_strided<SM_MID_I32>(pl, KID_DEC_MID, grid, st, s1, none));
         cur = pl->buf_c;
     }
     StridedArgs s = strided_base(pl, r, pl->npass - 1);
     s.src = cur; s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
     s.scales = scales; s.scales_stride = 0; s.eps_party0 = party;
-    FO_TRY(launch(pl, KID_DEC_HIGH, (k_strided<SM_DEC_LAST>), grid, block, st, s, none));
+    FO_TRY(launch_strided<SM_DEC_LAST>(pl, KID_DEC_HIGH, grid, st, s, none));
     return FO_OK;
 }
 
@@ -403,7 +412,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.scales = scales_up; s.scales_stride = pl->nblocks;
         s.gbar = gbar_or_null;
         s.M = M; s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
-        FO_TRY(launch(pl, KID_SERVER_HIGH, (k_strided<SM_SERVER>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, s, none));
+        FO_TRY(launch_strided<SM_SERVER>(pl, KID_SERVER_HIGH, dim3((unsigned)pl->ntiles, 1), st, s, none));
     }
     {
         ContigArgs c = contig_base(pl, r);

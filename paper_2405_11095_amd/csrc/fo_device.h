@@ -72,11 +72,12 @@ __device__ __forceinline__ float flip_if(float x, uint32_t bit) // bit in {0,1}
     return __uint_as_float(__float_as_uint(x) ^ (bit << 31));
 }
 
-template <typename T, int BIT>
-__device__ __forceinline__ void bfly(T (&v)[kV])
+template <typename T, int BIT, int V = kV>
+__device__ __forceinline__ void bfly(T (&v)[V])
 {
+    static_assert((1 << BIT) < V, "stage bit outside the register index");
 #pragma unroll
-    for (int r = 0; r < kV; ++r)
+    for (int r = 0; r < V; ++r)
         if (!(r & (1 << BIT))) {
             const T a = v[r], b = v[r | (1 << BIT)];
             v[r] = a + b;
@@ -90,6 +91,25 @@ __device__ __forceinline__ float wave_sum(float s, int steps) // butterfly sum o
     for (int k = 0; k < 6; ++k)
         if (k < steps) s += __shfl_xor(s, 1 << k, 64);
     return s;
+}
+
+// One Walsh-Hadamard stage on lane bit 5 (partner = lane ^ 32).  v_permlane32_swap trades the
+// upper half-wave of its first operand with the lower half-wave of its second, which brings both
+// ends of a butterfly into one lane; a second swap restores the layout.
+template <typename T, int V>
+__device__ __forceinline__ void bfly_lane5(T (&v)[V])
+{
+#pragma unroll
+    for (int k = 0; k < V / 2; ++k) {
+        uint32_t a = __builtin_bit_cast(uint32_t, v[k]), b = __builtin_bit_cast(uint32_t, v[k + V / 2]);
+        auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+        const T x = __builtin_bit_cast(T, (uint32_t)r[0]), y = __builtin_bit_cast(T, (uint32_t)r[1]);
+        a = __builtin_bit_cast(uint32_t, (T)(x + y));
+        b = __builtin_bit_cast(uint32_t, (T)(x - y));
+        r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+        v[k] = __builtin_bit_cast(T, (uint32_t)r[0]);
+        v[k + V / 2] = __builtin_bit_cast(T, (uint32_t)r[1]);
+    }
 }
 
 // Swap register bit 5 with lane bit 5: afterwards v[k] of the upper half-wave and v[k+32] of

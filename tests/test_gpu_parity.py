@@ -32,6 +32,8 @@ CASES = [
     ("blocked_b4096", 1 << 18, 2, 12, "layered"),
     ("blocked_b16384", (1 << 18) + 77, 2, 14, "layered"),
     ("blocked_b65536", (1 << 19) + 5, 2, 16, "layered"),
+    # the benchmark's geometry (n = 2^25: ten strided stages, the specialised kernels), fewer workers
+    ("c3_geometry_n2p25", 25_557_032, 3, 0, "heavy"),
 ]
 
 
