@@ -258,6 +258,18 @@ int launch_strided(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const Stride
     return launch(pl, kid, k_strided<MODE, 6, 0>, grid, dim3(SLayout<6>::T), st, s, tab);
 }
 
+// The packing kernels are compiled per (dither on/off, transform length below 256).
+template <int IN>
+int launch_pack(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigArgs &c, const PtrTab &tab)
+{
+    const bool dither = c.dither == FO_DITHER_UNIFORM, small = c.S < 8;
+    const dim3 block(kThreads);
+    if (dither && c.S == 15) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 15>, grid, block, st, c, tab);
+    if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true>, grid, block, st, c, tab);
+    if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false>, grid, block, st, c, tab);
+    return launch(pl, kid, k_contig<IN, OUT_PACK, false, false>, grid, block, st, c, tab);
+}
+
 StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
 {
     StridedArgs s;
@@ -306,7 +318,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
         c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
         c.len_in = len_in;
         c.compute_scale = scales_given ? 0u : 1u;
-        FO_TRY(launch(pl, KID_ENC_SINGLE, (k_contig<IN_GRAD, OUT_PACK>), grid, block, st, c, tb));
+        FO_TRY(launch_pack<IN_GRAD>(pl, KID_ENC_SINGLE, grid, st, c, tb));
         return FO_OK;
     }
     // transform lengths above 2^15: high stages first (eps flip and norm on load), low stages last
@@ -327,7 +339,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
                            pl->ntiles, (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda, scales, scales_stride));
     }
     c.src = tmp; c.src_stride = tmp_stride;
-    FO_TRY(launch(pl, KID_ENC_LOW, (k_contig<IN_F32, OUT_PACK>), grid, block, st, c, none));
+    FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid, st, c, none));
     return FO_OK;
 }
 
@@ -346,11 +358,12 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     c.party0 = party; c.eps_party0 = party;
     if (pl->npass == 0) {
         c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
-        FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32>), grid, block, st, c, none));
+        if (c.S == 15) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 15>), grid, block, st, c, none));
+        else FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32>), grid, block, st, c, none));
         return FO_OK;
     }
     c.dst = tmp; c.dst_stride = 0;
-    FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32>), grid, block, st, c, none));
+    FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), grid, block, st, c, none));
     const void *cur = tmp;
     if (pl->npass == 2) {
         StridedArgs s1 = strided_base(pl, r, 0);
@@ -403,7 +416,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         ContigArgs c = contig_base(pl, r);
         c.src = bits_up; c.src_stride = pl->W;
         c.dst = pl->buf_a; c.dst_stride = pl->ntot;
-        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c, none));
+        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c, none));
     }
     {
         StridedArgs s = strided_base(pl, r, 0);
@@ -420,7 +433,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         c.dst = bits_down; c.dst_stride = 0;
         c.scales = scales_down; c.scales_stride = 0;
         c.party0 = FO_PARTY_SERVER; c.eps_party0 = FO_PARTY_SERVER;
-        FO_TRY(launch(pl, KID_ENC_LOW, (k_contig<IN_F32, OUT_PACK>), dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, c, none));
+        FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, dim3((unsigned)pl->ntiles, 1), st, c, none));
     }
     return FO_OK;
 }

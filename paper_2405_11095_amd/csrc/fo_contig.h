@@ -51,7 +51,12 @@ struct ContigArgs {
     float delta;            // STORE_AXPY: x -= delta * value
 };
 
-template <int IN, int OUT>
+// DITHER: uniform dither on (OUT_PACK only).  SMALLB: transform length 64 or 128, where the four
+// registers that share a dither draw belong to different blocks.  Both are compile-time so that the
+// per-value code is branch free.
+// SC > 0: compiled for exactly SC stages inside the tile (SC = 15: transform length >= 2^15), which
+// makes every stage unconditional; SC = 0 reads the stage count from the arguments.
+template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0>
 __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
 {
     using T = typename std::conditional<IN == IN_BITS, int32_t, float>::type;
@@ -64,7 +69,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x, slot = blockIdx.y;
     const uint64_t base = (uint64_t)tile << kTileLog2;
-    const uint32_t S = a.S;
+    const uint32_t S = SC ? (uint32_t)SC : a.S;
     const uint32_t party = (a.party0 == 0xFFFFFFFFu) ? a.party0 : a.party0 + slot;
     const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
     const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
@@ -254,16 +259,18 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
         for (int g = 0; g < 16; ++g) {
             uint32_t w[4] = { 0u, 0u, 0u, 0u };
             const uint32_t lg = local_of(2 * g); // b6 = b7 = 0
-            if (a.dither == 0u) philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_dit, w);
             float thr_g = 0.f;
-            if (S >= 8u) thr_g = lam[lg >> S] * tscale;
+            if constexpr (DITHER) {
+                philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_dit, w);
+                if constexpr (!SMALLB) thr_g = lam[lg >> S] * tscale;
+            }
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const int r = 2 * g + (s & 1) + 32 * (s >> 1); // slot s = b6 | b7 << 1
-                float thr = thr_g;
-                if (S < 8u) thr = lam[local_of(r) >> S] * tscale;
                 float tv = v[r];
-                if (a.dither == 0u) {
+                if constexpr (DITHER) {
+                    float thr = thr_g;
+                    if constexpr (SMALLB) thr = lam[local_of(r) >> S] * tscale;
                     const int32_t m = (int32_t)((w[s] >> 8) << 1) - 16777215; // 2 r + 1 - 2^24
                     tv = fmaf(thr, (float)m, tv);
                 }

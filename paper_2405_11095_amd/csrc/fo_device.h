@@ -43,12 +43,13 @@ __device__ __forceinline__ void philox(uint32_t counter, const RngKey &key, uint
     uint32_t ka = key.k0, kb = key.k1;
 #pragma unroll
     for (int i = 0; i < 10; ++i) {
-        const uint32_t lo_a = x0 * 0xD2511F53u, hi_a = __umulhi(x0, 0xD2511F53u);
-        const uint32_t lo_b = x2 * 0xCD9E8D57u, hi_b = __umulhi(x2, 0xCD9E8D57u);
-        x0 = hi_b ^ x1 ^ ka;
-        x2 = hi_a ^ x3 ^ kb;
-        x1 = lo_b;
-        x3 = lo_a;
+        // full 64-bit products: one v_mad_u64_u32 each instead of a low and a high multiply
+        const uint64_t pa = (uint64_t)x0 * 0xD2511F53u;
+        const uint64_t pb = (uint64_t)x2 * 0xCD9E8D57u;
+        x0 = (uint32_t)(pb >> 32) ^ x1 ^ ka;
+        x2 = (uint32_t)(pa >> 32) ^ x3 ^ kb;
+        x1 = (uint32_t)pb;
+        x3 = (uint32_t)pa;
         ka += 0x9E3779B9u;
         kb += 0xBB67AE85u;
     }
