@@ -11,7 +11,7 @@
  * Conventions common to all calls
  *   - Every pointer named "device" is a device (HBM) pointer owned by the caller.  The library
  *     never frees or keeps them beyond the call's enqueued work.  Alignment (FO_EALIGN otherwise):
- *     gradients g and gbar 16 bytes, packed words 8 bytes, scales / out / x 4 bytes.  Host
+ *     fp32 vectors (g, gbar, out, x) 16 bytes, packed words 8 bytes, scales 4 bytes.  Host
  *     pointers are said to be host.
  *   - All work is enqueued on the caller's HIP stream (a hipStream_t passed as void*; NULL is the
  *     default stream).  The hot calls (fo_encode, fo_decode, fo_server_aggregate, fo_step) do

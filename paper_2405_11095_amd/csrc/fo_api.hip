@@ -228,10 +228,34 @@ Rng rng_of(const fo_plan *pl, uint64_t round)
     return { (uint32_t)pl->p.seed, (uint32_t)(pl->p.seed >> 32) ^ (uint32_t)(round >> 32), (uint32_t)round };
 }
 
+// Host-side guard against launching a kernel with a pointer it will dereference left unset.
+inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
+{
+    const bool grad_in = kid == KID_ENC_SINGLE;
+    if (!c.dst) return false;
+    if (grad_in ? (c.use_tab ? !tab.p[0] : !c.src) : !c.src) return false;
+    const bool needs_scales = kid == KID_ENC_SINGLE || kid == KID_ENC_LOW || kid == KID_DEC_SINGLE;
+    return !needs_scales || c.scales != nullptr;
+}
+inline bool args_ok(const StridedArgs &s, const PtrTab &tab, int kid)
+{
+    if (!s.dst) return false;
+    if (kid == KID_ENC_HIGH ? (s.use_tab ? !tab.p[0] : !s.src) : !s.src) return false;
+    if (kid == KID_ENC_HIGH && !s.partials) return false;
+    if ((kid == KID_DEC_HIGH || kid == KID_SERVER_HIGH) && !s.scales) return false;
+    return s.hb >= 1 && s.hb <= 10 && s.ls >= (uint32_t)kTileLog2;
+}
+template <typename... Args>
+inline bool args_ok(const Args &...) { return true; }
+
 // Enqueue one kernel; with profiling on, bracket it with two HIP events on the same stream.
 template <typename Kern, typename... Args>
 int launch(fo_plan *pl, int kid, Kern kernel, dim3 grid, dim3 block, hipStream_t st, Args... args)
 {
+    if (!args_ok(args..., kid)) {
+        std::snprintf(g_hip_err, sizeof(g_hip_err), "internal: unset kernel argument for %s", kKernelNames[kid]);
+        return FO_EHIP;
+    }
     Profiler &pf = pl->prof;
     const bool rec = pf.on && pf.used < Profiler::kMax;
     if (rec && !hip_ok(hipEventRecord(pf.ev[2 * pf.used], st), "hipEventRecord")) return FO_EHIP;
@@ -250,12 +274,12 @@ int launch(fo_plan *pl, int kid, Kern kernel, dim3 grid, dim3 block, hipStream_t
     } while (0)
 
 // Strided kernels come in a generic form and one compiled for ten stages next to the contiguous tile.
-template <int MODE>
+template <int MODE, bool IN16 = false>
 int launch_strided(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const StridedArgs &s, const PtrTab &tab)
 {
     if (s.hb == 10 && s.ls == (uint32_t)kTileLog2)
-        return launch(pl, kid, k_strided<MODE, 6, 10>, grid, dim3(SLayout<6>::T), st, s, tab);
-    return launch(pl, kid, k_strided<MODE, 6, 0>, grid, dim3(SLayout<6>::T), st, s, tab);
+        return launch(pl, kid, k_strided<MODE, 10, IN16>, grid, dim3(kThreads), st, s, tab);
+    return launch(pl, kid, k_strided<MODE, 0, IN16>, grid, dim3(kThreads), st, s, tab);
 }
 
 // The packing kernels are compiled per (dither on/off, transform length below 256).
@@ -356,6 +380,8 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     c.src = bits; c.src_stride = 0;
     c.scales = const_cast<float *>(scales); c.scales_stride = 0;
     c.party0 = party; c.eps_party0 = party;
+    // the decode-side transforms carry every value divided by two (see fo_contig.h)
+    out_coef *= 2.f;
     if (pl->npass == 0) {
         c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
         if (c.S == 15) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 15>), grid, block, st, c, none));
@@ -363,17 +389,21 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
         return FO_OK;
     }
     c.dst = tmp; c.dst_stride = 0;
-    FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), grid, block, st, c, none));
-    const void *cur = tmp;
-    if (pl->npass == 2) {
-        StridedArgs s1 = strided_base(pl, r, 0);
-        s1.src = tmp; s1.dst = pl->buf_c;
-        FO_TRY(launch_strided<SM_MID_I32>(pl, KID_DEC_MID, grid, st, s1, none));
-        cur = pl->buf_c;
-    }
     StridedArgs s = strided_base(pl, r, pl->npass - 1);
-    s.src = cur; s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
+    s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
     s.scales = scales; s.scales_stride = 0; s.eps_party0 = party;
+    if (pl->npass == 1) {
+        // int16 intermediate between the two passes
+        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I16, false, false, 15>), grid, block, st, c, none));
+        s.src = tmp;
+        FO_TRY((launch_strided<SM_DEC_LAST, true>(pl, KID_DEC_HIGH, grid, st, s, none)));
+        return FO_OK;
+    }
+    FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), grid, block, st, c, none));
+    StridedArgs s1 = strided_base(pl, r, 0);
+    s1.src = tmp; s1.dst = pl->buf_c;
+    FO_TRY(launch_strided<SM_MID_I32>(pl, KID_DEC_MID, grid, st, s1, none));
+    s.src = pl->buf_c;
     FO_TRY(launch_strided<SM_DEC_LAST>(pl, KID_DEC_HIGH, grid, st, s, none));
     return FO_OK;
 }
@@ -416,7 +446,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         ContigArgs c = contig_base(pl, r);
         c.src = bits_up; c.src_stride = pl->W;
         c.dst = pl->buf_a; c.dst_stride = pl->ntot;
-        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c, none));
+        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I16, false, false, 15>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c, none));
     }
     {
         StridedArgs s = strided_base(pl, r, 0);
@@ -424,8 +454,8 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.dst = pl->buf_b;
         s.scales = scales_up; s.scales_stride = pl->nblocks;
         s.gbar = gbar_or_null;
-        s.M = M; s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
-        FO_TRY(launch_strided<SM_SERVER>(pl, KID_SERVER_HIGH, dim3((unsigned)pl->ntiles, 1), st, s, none));
+        s.M = M; s.out_coef = 2.f * mean_coef; s.eps_party0 = FO_PARTY_SERVER; // int16 input holds half values
+        FO_TRY((launch_strided<SM_SERVER, true>(pl, KID_SERVER_HIGH, dim3((unsigned)pl->ntiles, 1), st, s, none)));
     }
     {
         ContigArgs c = contig_base(pl, r);
@@ -472,7 +502,7 @@ extern "C" int fo_decode(fo_plan *pl, const uint64_t *bits, const float *scales,
 {
     if (!pl || !bits || !scales || !out) return FO_EINVAL;
     if (party != FO_PARTY_SERVER && party >= pl->p.M) return FO_EINVAL;
-    if (!aligned(bits, 8) || !aligned(scales, 4) || !aligned(out, 4)) return FO_EALIGN;
+    if (!aligned(bits, 8) || !aligned(scales, 4) || !aligned(out, 16)) return FO_EALIGN;
     return launch_decode(pl, bits, scales, round, party, out, pl->p.d, STORE_SET, pl->rsqrtb, 0.f, pl->buf_a,
                          static_cast<hipStream_t>(hip_stream));
 }
@@ -491,7 +521,7 @@ extern "C" int fo_server_aggregate(fo_plan *pl, const uint64_t *bits_up, const f
 extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta, uint64_t round, void *hip_stream)
 {
     if (!pl || !g || !x) return FO_EINVAL;
-    if (!aligned(x, 4)) return FO_EALIGN;
+    if (!aligned(x, 16)) return FO_EALIGN;
     PtrTab tab;
     std::memset(&tab, 0, sizeof(tab));
     for (uint32_t m = 0; m < pl->p.M; ++m) {

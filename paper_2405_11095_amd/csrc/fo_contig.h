@@ -9,6 +9,12 @@
 //   L0 (global loads, 16 B per lane): regs = (b0,b1,b8,b9,b10,b11) lanes = (b2..b7)   waves = (b12,b13,b14)
 //   L1 (after the intra-wave exchange): regs = (b2..b7)            lanes = (b0,b1,b8,b9,b10,b11)
 //   L2 (after the cross-wave exchange): regs = (b6,b8,b12,b13,b14,b7) lanes = (b0..b5) waves = (b9,b10,b11)
+// (OUT_I16 reads the second exchange as lanes = (b1..b6), regs = (b0,b8,b12,b13,b14,b7) instead, so that a
+// thread owns pairs of neighbouring coordinates and stores them as one dword.)
+// The decode side (IN_BITS) carries every value divided by two: the stage on b0 is fused into the
+// unpacking as (c0 + c1 - 1, c0 - c1) for sign bits c0, c1, which is half the butterfly of the +-1
+// values, so after all fifteen stages the values fit int16 exactly; consumers fold the factor two
+// into their scale.
 // In L2 a wave holds 64 consecutive coordinates per register, so one compare per register yields
 // a packed 64-bit word, and the four registers that differ in (b6,b7) share one dither draw.
 // b7 keeps register bit 5 across the second exchange, so each half of it can run in place.
@@ -18,7 +24,7 @@
 namespace fo {
 
 enum { IN_GRAD = 0, IN_F32 = 1, IN_BITS = 2 };
-enum { OUT_PACK = 0, OUT_I32 = 1, OUT_F32 = 2 };
+enum { OUT_PACK = 0, OUT_I32 = 1, OUT_F32 = 2, OUT_I16 = 3 };
 enum { STORE_SET = 0, STORE_ACC = 1, STORE_AXPY = 2 };
 
 struct PtrTab {
@@ -28,7 +34,7 @@ struct PtrTab {
 struct ContigArgs {
     const void *src;        // IN_F32: fp32 [slot][ntot]; IN_BITS: uint64 [slot][W]; IN_GRAD: unused if use_tab
     uint64_t src_stride;    // elements between party slots
-    void *dst;              // OUT_PACK: uint64 [slot][W]; OUT_I32: int32 [slot][ntot]; OUT_F32: fp32 [len_out]
+    void *dst;              // OUT_PACK: uint64 [slot][W]; OUT_I32 / OUT_I16: int [slot][ntot]; OUT_F32: fp32 [len_out]
     uint64_t dst_stride;
     float *scales;          // [slot][nblocks]
     uint64_t scales_stride;
@@ -102,8 +108,12 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
             const uint64_t gw = (uint64_t)tile * 512u + wave * 64u + c * 4u + (lane >> 4);
             const uint64_t w = (gw < a.W) ? src[gw] : 0ull;
             const uint32_t nib = (uint32_t)(w >> ((lane & 15u) * 4u));
-#pragma unroll
-            for (int k = 0; k < 4; ++k) v[4 * c + k] = (int32_t)(((nib >> k) & 1u) << 1) - 1;
+            // half of the b0 butterfly of the +-1 values (2 c - 1): sum / 2 = c0 + c1 - 1, difference / 2 = c0 - c1
+            const int32_t c0 = nib & 1u, c1 = (nib >> 1) & 1u, c2 = (nib >> 2) & 1u, c3 = (nib >> 3) & 1u;
+            v[4 * c + 0] = c0 + c1 - 1;
+            v[4 * c + 1] = c0 - c1;
+            v[4 * c + 2] = c2 + c3 - 1;
+            v[4 * c + 3] = c2 - c3;
         }
     }
 
@@ -154,7 +164,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
     }
 
     // ------------------------------------------------------------------ round 1: b0,b1,b8..b11
-    bfly<T, 0>(v);
+    if constexpr (IN != IN_BITS) bfly<T, 0>(v); // the decode side did this stage while unpacking
     bfly<T, 1>(v);
     if (S > 8u) bfly<T, 2>(v);
     if (S > 9u) bfly<T, 3>(v);
@@ -190,7 +200,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
     // ------------------------------------------------------------------ amplitudes of the tile's blocks
     const uint32_t nblk_tile = kTile >> S;
     const uint64_t blk0 = (a.logb <= (uint32_t)kTileLog2) ? (uint64_t)tile * nblk_tile : (base >> a.logb);
-    if constexpr (OUT != OUT_I32) {
+    if constexpr (OUT == OUT_PACK || OUT == OUT_F32) { // the integer intermediates carry no amplitude
         if (t < nblk_tile) {
             float l = 0.f;
             const uint64_t gb = blk0 + t;
@@ -233,10 +243,21 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
 #pragma unroll
             for (int r = 0; r < 32; ++r) xbuf[wofs + r * 4] = __builtin_bit_cast(uint32_t, v[sub * 32 + r]);
             __syncthreads();
+            if constexpr (OUT == OUT_I16) {
+                // lanes = (b1..b6): a lane reads the pair b0 = 0, 1 (8 bytes); register sub*32 + q = (b0,b8,b12,b13,b14 | b7)
+                const uint2 *rp2 = reinterpret_cast<const uint2 *>(xbuf) + (lane + wave * 132u);
 #pragma unroll
-            for (int q = 0; q < 32; ++q) // register sub*32 + q = (b6,b8,b12,b13,b14 | b7 = sub)
-                v[sub * 32 + q] =
-                    __builtin_bit_cast(T, xbuf[rofs + (q & 1) * 64 + (((q >> 1) & 1) + (q >> 2) * 16) * 132]);
+                for (int q = 0; q < 32; q += 2) {
+                    const uint2 d = rp2[(((q >> 1) & 1) + (q >> 2) * 16) * 66];
+                    v[sub * 32 + q] = __builtin_bit_cast(T, d.x);
+                    v[sub * 32 + q + 1] = __builtin_bit_cast(T, d.y);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 32; ++q) // register sub*32 + q = (b6,b8,b12,b13,b14 | b7 = sub)
+                    v[sub * 32 + q] =
+                        __builtin_bit_cast(T, xbuf[rofs + (q & 1) * 64 + (((q >> 1) & 1) + (q >> 2) * 16) * 132]);
+            }
         }
     }
 
@@ -286,6 +307,16 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
                             ((lane & 1u) | ((lane >> 5) << 1) | (((lane >> 1) & 1u) << 2) | (wave << 3) | (((lane >> 2) & 7u) << 6));
         if (gw < a.W)
             static_cast<uint64_t *>(a.dst)[slot * a.dst_stride + gw] = ((uint64_t)my_hi << 32) | my_lo;
+    } else if constexpr (OUT == OUT_I16) {
+        // pairs (b0 = 0, 1) packed into one dword; a wave writes 256 contiguous bytes per register pair
+        uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<int16_t *>(a.dst) + slot * a.dst_stride + base);
+#pragma unroll
+        for (int r = 0; r < kV; r += 2) {
+            // dword index = coordinate / 2 = lane | b7 << 6 | b8 << 7 | wave << 8 | (b12..b14) << 11
+            const uint32_t di = lane | ((uint32_t)(r >> 5) << 6) | ((uint32_t)((r >> 1) & 1) << 7) | (wave << 8) |
+                                ((uint32_t)((r >> 2) & 7) << 11);
+            dst[di] = __builtin_amdgcn_perm((uint32_t)v[r + 1], (uint32_t)v[r], 0x05040100u);
+        }
     } else if constexpr (OUT == OUT_I32) {
         int32_t *dst = static_cast<int32_t *>(a.dst) + slot * a.dst_stride + base;
 #pragma unroll

@@ -1,20 +1,21 @@
 // Strided-tile kernel: up to ten Walsh-Hadamard stages on index bits above the contiguous tile
 // (transform lengths above 2^15).  A tile is R = 2^hb rows by 2^(15-hb) consecutive columns, rows
-// 2^ls coordinates apart; the stages act along the rows' axis only.  Global accesses are one
-// dword per lane; a wave touches 64 consecutive columns (256 B), or 2 x 32 when hb = 10.
+// 2^ls coordinates apart; the stages act along the rows' axis only.
 //
-// Tile coordinate u = row << cb | col (cb = 15 - hb).  With V = 2^LV values per thread and
-// NW = 9 - LV wave bits (V = 64: 512 threads; V = 32: 1024 threads):
-//   LA (loads):              lanes = (u0..u5)  waves = (u6..u5+NW)        regs = (u6+NW..u14)
-//   LB (after the exchange): lanes = (u0..u5)  waves = (u6+NW..u5+2NW)    regs = (u6..u5+NW, u6+2NW..u14)
-// The exchange swaps the wave bits with the low NW register bits through LDS; lanes keep their
-// bits, so LDS accesses are conflict free and global stores stay as coalesced as the loads.  A row
-// bit that falls on lane bit 5 (hb = 10) is handled with v_permlane32_swap.
+// Tile coordinate u = row << cb | col (cb = 15 - hb >= 5).  512 threads hold 64 values each, as 32
+// pairs of neighbouring columns, so every global access moves a pair: 8 bytes per lane for fp32,
+// 4 bytes per lane for the int16 intermediate that the decode side reads.
+//   LA (loads):              reg0 = u0  lanes = (u1..u6)  waves = (u7,u8,u9)     regs 1..5 = (u10..u14)
+//   LB (after the exchange): reg0 = u0  lanes = (u1..u6)  waves = (u10,u11,u12)  regs 1..5 = (u7,u8,u9,u13,u14)
+// The exchange swaps the wave bits with register bits 1..3 through LDS in two halves (register
+// bit 5 picks the half); lanes keep their bits, so LDS traffic is 8 bytes per lane, conflict free,
+// and stores are as coalesced as loads.  Row bits that fall on lane bits 4 and 5 (hb >= 9) are
+// handled with v_permlane16_swap / v_permlane32_swap.
 // Modes
 //   SM_ENC_FIRST : fp32 gradient (zero padded), eps flip on load, tile sum of squares -> fp32 intermediate
-//   SM_DEC_LAST  : int32 intermediate -> lambda/sqrt(b) scaling, eps flip, store / SGD update (Def. 3.8)
+//   SM_DEC_LAST  : integer intermediate -> lambda/sqrt(b) scaling, eps flip, store / SGD update (Def. 3.8)
 //   SM_MID       : intermediate in, intermediate out (three-pass transforms)
-//   SM_SERVER    : for every worker: int32 intermediate -> remaining inverse stages, scale, flip,
+//   SM_SERVER    : for every worker: int16 intermediate -> remaining inverse stages, scale, flip,
 //                  accumulate the mean (eq. "server average"); then eps^s flip and the forward
 //                  stages of the re-encode (Sec. 4, server-to-workers encoding) -> fp32 intermediate
 #pragma once
@@ -25,9 +26,9 @@ namespace fo {
 enum { SM_ENC_FIRST = 0, SM_DEC_LAST = 1, SM_MID_F32 = 2, SM_MID_I32 = 3, SM_SERVER = 4 };
 
 struct StridedArgs {
-    const void *src;       // fp32 / int32 [slot][ntot] (ENC_FIRST: gradients, or pointer table)
-    uint64_t src_stride;
-    void *dst;             // fp32 / int32 [slot][ntot]; DEC_LAST: fp32 [len_out]
+    const void *src;       // [slot][ntot] fp32 / int32 / int16 (ENC_FIRST: gradients, or pointer table)
+    uint64_t src_stride;   // elements between slots
+    void *dst;             // [slot][ntot] fp32 / int32; DEC_LAST: fp32 [len_out]
     uint64_t dst_stride;
     const float *scales;   // [slot or worker][nblocks]
     uint64_t scales_stride;
@@ -41,13 +42,13 @@ struct StridedArgs {
     uint32_t store_mode;
     uint32_t eps_party0;
     uint32_t k0, k1, round_lo;
-    float out_coef;        // 1/sqrt(b) (times 1/M in SERVER)
+    float out_coef;        // value = lambda * out_coef * (transformed integer)
     float delta;
 };
 
 // Element offset of tile coordinate u from the tile origin.  Each bit of u has a fixed weight
 // (column bits keep theirs, row bits move up to the row stride), so off(u1 | u2) = off(u1) + off(u2)
-// for disjoint bit sets: a thread adds its own part once and a wave-uniform part per register.
+// for disjoint bit sets: a thread adds its own part once and a wave-uniform part per register pair.
 struct StridedGeom {
     uint64_t origin; // coordinate of u = 0
     uint32_t cb, ls;
@@ -57,43 +58,36 @@ struct StridedGeom {
     }
 };
 
-// Access through a wave-uniform base pointer plus a 32-bit per-lane byte offset: this is the
-// address form that needs one offset register per thread instead of a 64-bit address per access.
-template <typename T>
-__device__ __forceinline__ T ld_at(const T *uniform_base, uint32_t byte_off)
+constexpr int kSV = 64;        // values per thread
+constexpr int kSP = kSV / 2;   // pairs per thread
+
+// thread part and (wave-uniform) pair part of a tile coordinate; p = register number >> 1
+__device__ __forceinline__ uint32_t sa_thread(uint32_t lane, uint32_t wave) { return (lane << 1) | (wave << 7); }
+__device__ __forceinline__ constexpr uint32_t sa_pair(int p) { return (uint32_t)p << 10; }
+__device__ __forceinline__ uint32_t sb_thread(uint32_t lane, uint32_t wave) { return (lane << 1) | (wave << 10); }
+__device__ __forceinline__ constexpr uint32_t sb_pair(int p)
 {
-    return *reinterpret_cast<const T *>(reinterpret_cast<const char *>(uniform_base) + byte_off);
-}
-template <typename T>
-__device__ __forceinline__ T &ref_at(T *uniform_base, uint32_t byte_off)
-{
-    return *reinterpret_cast<T *>(reinterpret_cast<char *>(uniform_base) + byte_off);
+    return ((uint32_t)(p & 7) << 7) | ((uint32_t)(p >> 3) << 13);
 }
 
-template <int LV>
-struct SLayout {
-    static constexpr int V = 1 << LV;
-    static constexpr int T = (int)kTile >> LV;
-    static constexpr int NW = 9 - LV;                 // wave bits
-    static constexpr int NS = LV - NW;                // register bits the exchange leaves alone
-    static_assert(NS >= 1, "the exchange is split in two halves on a spectator register bit");
-    // thread part and (wave-uniform) register part of a tile coordinate in the two layouts
-    static __device__ __forceinline__ uint32_t ta(uint32_t lane, uint32_t wave) { return lane | (wave << 6); }
-    static __device__ __forceinline__ constexpr uint32_t ra(int r) { return (uint32_t)r << (6 + NW); }
-    static __device__ __forceinline__ uint32_t tb(uint32_t lane, uint32_t wave) { return lane | (wave << (6 + NW)); }
-    static __device__ __forceinline__ constexpr uint32_t rb(int r)
-    {
-        return ((uint32_t)(r & ((1 << NW) - 1)) << 6) | ((uint32_t)(r >> NW) << (6 + 2 * NW));
-    }
-};
+// Access through a wave-uniform base pointer plus a 32-bit per-lane byte offset.
+template <typename T>
+__device__ __forceinline__ T ld_at(const void *uniform_base, uint32_t byte_off)
+{
+    return *reinterpret_cast<const T *>(static_cast<const char *>(uniform_base) + byte_off);
+}
+template <typename T>
+__device__ __forceinline__ T &ref_at(void *uniform_base, uint32_t byte_off)
+{
+    return *reinterpret_cast<T *>(static_cast<char *>(uniform_base) + byte_off);
+}
 
 // eps words of the tile, one 32-bit word per group of 32 consecutive columns (u >> 5)
-template <int T>
 __device__ __forceinline__ void fill_eps(uint32_t *epsw, const StridedGeom &g, const RngKey &key, uint32_t t)
 {
 #pragma unroll
-    for (int h = 0; h < 1024 / T; ++h) {
-        const uint32_t grp = t + h * T;
+    for (int h = 0; h < 2; ++h) {
+        const uint32_t grp = t + h * kThreads;
         const uint64_t i = g.origin + g.off(grp << 5);
         uint32_t w[4];
         philox((uint32_t)(i >> 7), key, w);
@@ -102,102 +96,140 @@ __device__ __forceinline__ void fill_eps(uint32_t *epsw, const StridedGeom &g, c
     }
 }
 
-// stages on the register bits of LA (register bit k <-> u bit 6 + NW + k) and on lane bit 5
-template <typename T, int LV>
-__device__ __forceinline__ void stages_a(T (&v)[1 << LV], uint32_t cb)
+// One stage on lane bit 4 (partner = lane ^ 16): v_permlane16_swap trades the odd 16-lane rows of
+// its first operand with the even rows of its second.
+template <typename T, int V>
+__device__ __forceinline__ void bfly_lane4(T (&v)[V])
 {
-    constexpr int B0 = 6 + SLayout<LV>::NW, V = 1 << LV;
-    if (cb <= 5u) bfly_lane5<T, V>(v);
-    if (cb <= (uint32_t)B0) bfly<T, 0, V>(v);
-    if (cb <= (uint32_t)B0 + 1) bfly<T, 1, V>(v);
-    if (cb <= (uint32_t)B0 + 2) bfly<T, 2, V>(v);
-    if (cb <= (uint32_t)B0 + 3) bfly<T, 3, V>(v);
-    if constexpr (LV > 4) {
-        if (cb <= (uint32_t)B0 + 4) bfly<T, 4, V>(v);
-    }
-    if constexpr (LV > 5) {
-        if (cb <= (uint32_t)B0 + 5) bfly<T, 5, V>(v);
-    }
-}
-// stages on the low NW register bits of LB (register bit k <-> u bit 6 + k)
-template <typename T, int LV>
-__device__ __forceinline__ void stages_b(T (&v)[1 << LV], uint32_t cb)
-{
-    constexpr int NW = SLayout<LV>::NW, V = 1 << LV;
-    if (cb <= 6u) bfly<T, 0, V>(v);
-    if (cb <= 7u) bfly<T, 1, V>(v);
-    if (cb <= 8u) bfly<T, 2, V>(v);
-    if constexpr (NW > 3) {
-        if (cb <= 9u) bfly<T, 3, V>(v);
+#pragma unroll
+    for (int k = 0; k < V / 2; ++k) {
+        uint32_t a = __builtin_bit_cast(uint32_t, v[k]), b = __builtin_bit_cast(uint32_t, v[k + V / 2]);
+        auto r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+        const T x = __builtin_bit_cast(T, (uint32_t)r[0]), y = __builtin_bit_cast(T, (uint32_t)r[1]);
+        a = __builtin_bit_cast(uint32_t, (T)(x + y));
+        b = __builtin_bit_cast(uint32_t, (T)(x - y));
+        r = __builtin_amdgcn_permlane16_swap(a, b, false, false);
+        v[k] = __builtin_bit_cast(T, (uint32_t)r[0]);
+        v[k + V / 2] = __builtin_bit_cast(T, (uint32_t)r[1]);
     }
 }
 
-// LA <-> LB through LDS in two halves split on the top register bit (a spectator): the wave index
-// and the low NW register bits trade places (the map is its own inverse).
-// Word address: lane | wave-bits << 6 | low-register-bits << (6 + NW) | other spectators << (6 + 2 NW).
-template <typename T, int LV>
-__device__ __forceinline__ void exchange(T (&v)[1 << LV], uint32_t *xbuf, uint32_t lane, uint32_t wave)
+// stages on lane bits 4, 5 (u5, u6) and on register bits 1..5 of LA (u10..u14)
+template <typename T>
+__device__ __forceinline__ void stages_a(T (&v)[kSV], uint32_t cb)
 {
-    constexpr int V = 1 << LV, NW = SLayout<LV>::NW, H = V / 2;
-    const uint32_t wofs = lane | (wave << 6), rofs = lane | (wave << (6 + NW));
+    if (cb <= 5u) bfly_lane4<T, kSV>(v);
+    if (cb <= 6u) bfly_lane5<T, kSV>(v);
+    if (cb <= 10u) bfly<T, 1, kSV>(v);
+    if (cb <= 11u) bfly<T, 2, kSV>(v);
+    if (cb <= 12u) bfly<T, 3, kSV>(v);
+    if (cb <= 13u) bfly<T, 4, kSV>(v);
+    bfly<T, 5, kSV>(v);
+}
+// stages on register bits 1..3 of LB (u7, u8, u9)
+template <typename T>
+__device__ __forceinline__ void stages_b(T (&v)[kSV], uint32_t cb)
+{
+    if (cb <= 7u) bfly<T, 1, kSV>(v);
+    if (cb <= 8u) bfly<T, 2, kSV>(v);
+    if (cb <= 9u) bfly<T, 3, kSV>(v);
+}
+
+// LA <-> LB through LDS in two halves split on register bit 5 (a spectator): the wave index and
+// register bits 1..3 trade places (the map is its own inverse).  A lane moves a pair (8 bytes).
+// Word address: u0 | lane << 1 | wave-bits << 7 | register-bits-1..3 << 10 | register-bit-4 << 13.
+template <typename T>
+__device__ __forceinline__ void exchange(T (&v)[kSV], uint32_t *xbuf, uint32_t lane, uint32_t wave)
+{
+    uint2 *const wp = reinterpret_cast<uint2 *>(xbuf) + (lane | (wave << 6));
+    uint2 *const rp = reinterpret_cast<uint2 *>(xbuf) + (lane | (wave << 9));
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
         if (sub) __syncthreads();
 #pragma unroll
-        for (int r = 0; r < H; ++r)
-            xbuf[wofs + ((r & ((1 << NW) - 1)) << (6 + NW)) + ((r >> NW) << (6 + 2 * NW))] =
-                __builtin_bit_cast(uint32_t, v[sub * H + r]);
+        for (int p = 0; p < 16; ++p) // pair p of this half: register bits 1..3 = p & 7, bit 4 = p >> 3
+            wp[((p & 7) << 9) | ((p >> 3) << 12)] =
+                make_uint2(__builtin_bit_cast(uint32_t, v[sub * 32 + 2 * p]), __builtin_bit_cast(uint32_t, v[sub * 32 + 2 * p + 1]));
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < H; ++r)
-            v[sub * H + r] =
-                __builtin_bit_cast(T, xbuf[rofs + ((r & ((1 << NW) - 1)) << 6) + ((r >> NW) << (6 + 2 * NW))]);
+        for (int p = 0; p < 16; ++p) {
+            const uint2 d = rp[((p & 7) << 6) | ((p >> 3) << 12)];
+            v[sub * 32 + 2 * p] = __builtin_bit_cast(T, d.x);
+            v[sub * 32 + 2 * p + 1] = __builtin_bit_cast(T, d.y);
+        }
     }
+}
+
+// flip a pair by bits 2k, 2k+1 of an eps word already shifted right by 2k
+__device__ __forceinline__ void flip_pair(float &x0, float &x1, uint32_t wshift)
+{
+    x0 = __uint_as_float(__float_as_uint(x0) ^ (wshift << 31));
+    x1 = __uint_as_float(__float_as_uint(x1) ^ ((wshift << 30) & 0x80000000u));
 }
 
 // HB = 0: the number of stages and the row stride are read from the arguments.  HB > 0: compiled
 // for exactly HB stages with rows 2^15 apart (the pass next to the contiguous tile), which turns
 // every per-register offset into a constant and removes the stage-selection branches.
-template <int MODE, int LV, int HB>
-__global__ __launch_bounds__(SLayout<LV>::T, (MODE == SM_SERVER ? 2 : 4)) void k_strided(const StridedArgs a, const PtrTab tab)
+// IN16: the integer input is the contiguous kernel's int16 intermediate.
+template <int MODE, int HB, bool IN16>
+__global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strided(const StridedArgs a, const PtrTab tab)
 {
-    using L = SLayout<LV>;
-    constexpr int V = L::V, T = L::T;
-    using TIN = typename std::conditional<(MODE == SM_ENC_FIRST || MODE == SM_MID_F32), float, int32_t>::type;
+    constexpr bool FIN = (MODE == SM_ENC_FIRST || MODE == SM_MID_F32); // fp32 input
+    using TV = typename std::conditional<FIN, float, int32_t>::type;
     __shared__ uint32_t lds[kLdsWords];
     uint32_t *const xbuf = lds;
     uint32_t *const epsw = lds + kXWords;
     float *const red = reinterpret_cast<float *>(lds + kXWords + kEpsWords + kLamWords);
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
+    const uint32_t slot = blockIdx.y;
     const uint32_t hb = HB ? (uint32_t)HB : a.hb;
     const uint32_t cb = (uint32_t)kTileLog2 - hb;
-    const bool need_x = cb < 6u + (uint32_t)L::NW;      // some row bit lives in the wave index
+    // 64-byte row segments (int16 input, 32 columns): neighbouring column groups share 128-byte lines, so
+    // they are given block indices that land on the same XCD (blocks are dealt round-robin over 8 XCDs)
+    uint32_t tile = blockIdx.x;
+    if (IN16 && cb == 5u) tile = (tile & ~15u) | ((tile & 7u) << 1) | ((tile >> 3) & 1u);
+    const bool need_x = cb <= 9u; // some row bit lives in the wave index
     StridedGeom g;
     g.cb = cb;
     g.ls = HB ? (uint32_t)kTileLog2 : a.ls;
     {
-        const uint32_t sh = g.ls - cb;                    // column groups per outer block = 2^sh
+        const uint32_t sh = g.ls - cb; // column groups per outer block = 2^sh
         const uint64_t outer = (uint64_t)tile >> sh, cg = tile & ((1u << sh) - 1u);
         g.origin = (outer << (g.ls + hb)) + (cg << cb);
     }
-    const uint64_t gb = g.origin >> a.logb;               // the tile lies inside one block
+    const uint64_t gb = g.origin >> a.logb; // the tile lies inside one block
 
     // thread parts of the tile coordinate and of the element offset in both layouts
-    const uint32_t uta = L::ta(lane, wave), utb = L::tb(lane, wave);
+    const uint32_t uta = sa_thread(lane, wave), utb = sb_thread(lane, wave);
     const uint32_t ota = g.off(uta), otb = g.off(utb);
     // layout in which the transformed tile is held: LB if the exchange ran, else LA
     const uint32_t ut_out = need_x ? utb : uta, ot_out = need_x ? otb : ota;
-    auto ureg_out = [&](int r) -> uint32_t { return need_x ? L::rb(r) : L::ra(r); };
-    const uint32_t ebit = lane & 31u;
-    const uint32_t oba = ota * 4u, ob_out = ot_out * 4u; // per-thread byte offsets (tiles span < 2^32 bytes)
+    auto upair_out = [&](int p) -> uint32_t { return need_x ? sb_pair(p) : sa_pair(p); };
+    const uint32_t eshift = (lane & 15u) << 1; // bit of column u0 = 0 inside its eps word
+
+    // ---- input of one tile (layout LA) as 32 pairs
+    auto load_int = [&](int32_t (&v)[kSV], const void *src_base) {
+#pragma unroll
+        for (int p = 0; p < kSP; ++p) {
+            const uint32_t ro = g.off(sa_pair(p)); // wave-uniform
+            if constexpr (IN16) {
+                const uint32_t d = ld_at<uint32_t>(static_cast<const int16_t *>(src_base) + ro, ota * 2u);
+                v[2 * p] = (int32_t)(int16_t)(d & 0xFFFFu);
+                v[2 * p + 1] = (int32_t)d >> 16;
+            } else {
+                const int2 d = ld_at<int2>(static_cast<const int32_t *>(src_base) + ro, ota * 4u);
+                v[2 * p] = d.x;
+                v[2 * p + 1] = d.y;
+            }
+        }
+    };
 
     if constexpr (MODE != SM_SERVER) {
-        TIN v[V];
+        TV v[kSV];
         const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
         const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
-        if constexpr (MODE == SM_ENC_FIRST || MODE == SM_DEC_LAST) fill_eps<T>(epsw, g, key_eps, t);
+        if constexpr (MODE == SM_ENC_FIRST || MODE == SM_DEC_LAST) fill_eps(epsw, g, key_eps, t);
 
         // ---------------------------------------------------------------- load (LA)
         if constexpr (MODE == SM_ENC_FIRST) {
@@ -205,38 +237,48 @@ __global__ __launch_bounds__(SLayout<LV>::T, (MODE == SM_SERVER ? 2 : 4)) void k
             const uint64_t room = a.len_in > g.origin ? a.len_in - g.origin : 0; // valid elements from the origin on
             src += g.origin;
 #pragma unroll
-            for (int r = 0; r < V; ++r) {
-                const uint32_t ro = g.off(L::ra(r));             // wave-uniform part
-                v[r] = ((uint64_t)ro + ota < room) ? ld_at(src + ro, oba) : 0.f;
+            for (int p = 0; p < kSP; ++p) {
+                const uint32_t ro = g.off(sa_pair(p)); // wave-uniform
+                const uint64_t e = (uint64_t)ro + ota;
+                float2 d = make_float2(0.f, 0.f);
+                if (e + 1 < room) d = ld_at<float2>(src + ro, ota * 4u);
+                else if (e < room) d.x = ld_at<float>(src + ro, ota * 4u);
+                v[2 * p] = d.x;
+                v[2 * p + 1] = d.y;
             }
             float acc = 0.f;
 #pragma unroll
-            for (int r = 0; r < V; r += 4)
+            for (int r = 0; r < kSV; r += 4)
                 acc += (v[r] * v[r] + v[r + 1] * v[r + 1]) + (v[r + 2] * v[r + 2] + v[r + 3] * v[r + 3]);
             acc = wave_sum(acc, 6);
             if (lane == 0) red[wave] = acc;
             __syncthreads(); // also publishes epsw
             if (t == 0) {
                 float s = 0.f;
-                for (int w = 0; w < T / 64; ++w) s += red[w];
+                for (int w = 0; w < kThreads / 64; ++w) s += red[w];
                 a.partials[(uint64_t)slot * gridDim.x + tile] = s;
             }
 #pragma unroll
-            for (int r = 0; r < V; ++r) {
-                const uint32_t w = epsw[(uta >> 5) + (L::ra(r) >> 5)];
-                v[r] = flip_if(v[r], (w >> ebit) & 1u);
+            for (int p = 0; p < kSP; ++p)
+                flip_pair(v[2 * p], v[2 * p + 1], epsw[(uta >> 5) + (sa_pair(p) >> 5)] >> eshift);
+        } else if constexpr (MODE == SM_MID_F32) {
+            const float *src = static_cast<const float *>(a.src) + slot * a.src_stride + g.origin;
+#pragma unroll
+            for (int p = 0; p < kSP; ++p) {
+                const float2 d = ld_at<float2>(src + g.off(sa_pair(p)), ota * 4u);
+                v[2 * p] = d.x;
+                v[2 * p + 1] = d.y;
             }
         } else {
-            const TIN *src = static_cast<const TIN *>(a.src) + slot * a.src_stride + g.origin;
-#pragma unroll
-            for (int r = 0; r < V; ++r) v[r] = ld_at(src + g.off(L::ra(r)), oba);
+            const char *src = static_cast<const char *>(a.src) + (slot * a.src_stride + g.origin) * (IN16 ? 2u : 4u);
+            load_int(v, src);
         }
 
         // ---------------------------------------------------------------- stages
-        stages_a<TIN, LV>(v, cb);
+        stages_a<TV>(v, cb);
         if (need_x) {
-            exchange<TIN, LV>(v, xbuf, lane, wave);
-            stages_b<TIN, LV>(v, cb);
+            exchange<TV>(v, xbuf, lane, wave);
+            stages_b<TV>(v, cb);
         } else if (MODE == SM_DEC_LAST) {
             __syncthreads(); // publishes epsw
         }
@@ -247,88 +289,121 @@ __global__ __launch_bounds__(SLayout<LV>::T, (MODE == SM_SERVER ? 2 : 4)) void k
             float *dst = static_cast<float *>(a.dst) + g.origin;
             const uint64_t room = a.len_out > g.origin ? a.len_out - g.origin : 0;
 #pragma unroll
-            for (int r = 0; r < V; ++r) {
-                const uint32_t ur = ureg_out(r);
-                const uint32_t ro = g.off(ur);                   // wave-uniform part
-                const float val = flip_if(c * (float)v[r], (epsw[(ut_out >> 5) + (ur >> 5)] >> ebit) & 1u);
-                if ((uint64_t)ro + ot_out < room) {
-                    float &q = ref_at(dst + ro, ob_out);
-                    if (a.store_mode == STORE_SET) q = val;
-                    else if (a.store_mode == STORE_ACC) q += val;
-                    else q -= a.delta * val;
+            for (int p = 0; p < kSP; ++p) {
+                const uint32_t up = upair_out(p);
+                const uint32_t ro = g.off(up); // wave-uniform
+                float y0 = c * (float)v[2 * p], y1 = c * (float)v[2 * p + 1];
+                flip_pair(y0, y1, epsw[(ut_out >> 5) + (up >> 5)] >> eshift);
+                const uint64_t e = (uint64_t)ro + ot_out;
+                if (e + 1 < room) {
+                    float2 &q = ref_at<float2>(dst + ro, ot_out * 4u);
+                    if (a.store_mode == STORE_SET) q = make_float2(y0, y1);
+                    else if (a.store_mode == STORE_ACC) q = make_float2(q.x + y0, q.y + y1);
+                    else q = make_float2(q.x - a.delta * y0, q.y - a.delta * y1);
+                } else if (e < room) {
+                    float &q = ref_at<float>(dst + ro, ot_out * 4u);
+                    if (a.store_mode == STORE_SET) q = y0;
+                    else if (a.store_mode == STORE_ACC) q += y0;
+                    else q -= a.delta * y0;
                 }
             }
         } else {
-            TIN *dst = static_cast<TIN *>(a.dst) + slot * a.dst_stride + g.origin;
+            TV *dst = static_cast<TV *>(a.dst) + slot * a.dst_stride + g.origin;
 #pragma unroll
-            for (int r = 0; r < V; ++r) ref_at(dst + g.off(ureg_out(r)), ob_out) = v[r];
+            for (int p = 0; p < kSP; ++p) {
+                using T2 = typename std::conditional<FIN, float2, int2>::type;
+                T2 d;
+                d.x = v[2 * p];
+                d.y = v[2 * p + 1];
+                ref_at<T2>(dst + g.off(upair_out(p)), ot_out * 4u) = d;
+            }
         }
     } else {
         // ==================================================================== server
-        float acc[V];
-        int32_t bufa[V], bufb[V]; // ping-pong: one tile is transformed while the next one travels
+        static_assert(IN16, "the server pass reads the int16 intermediate");
+        float acc[kSV];
+        uint32_t rawa[kSP], rawb[kSP]; // ping-pong of packed tiles: one is transformed while the next one travels
 #pragma unroll
-        for (int r = 0; r < V; ++r) acc[r] = 0.f;
-
-        // request registers [r0, r1) of worker m's tile
-        auto request = [&](int32_t (&buf)[V], uint32_t m, auto r0, auto r1) {
-            const int32_t *src = static_cast<const int32_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin;
+        for (int r = 0; r < kSV; ++r) acc[r] = 0.f;
+        auto request = [&](uint32_t (&raw)[kSP], uint32_t m) {
+            const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin;
 #pragma unroll
-            for (int r = decltype(r0)::value; r < decltype(r1)::value; ++r) buf[r] = ld_at(src + g.off(L::ra(r)), oba);
+            for (int p = 0; p < kSP; ++p) raw[p] = ld_at<uint32_t>(src + g.off(sa_pair(p)), ota * 2u);
         };
-        using I0 = std::integral_constant<int, 0>;
-        using IH = std::integral_constant<int, V / 2>;
-        using IV = std::integral_constant<int, V>;
-        // finish worker m (tile in `buf`) while worker m + 1 is requested into `nbuf` in two batches, so
-        // that the wait for `buf` never has more than V/2 younger loads in flight behind it
-        auto process = [&](int32_t (&buf)[V], int32_t (&nbuf)[V], uint32_t m) {
-            const bool more = m + 1 < a.M;
-            if (more) request(nbuf, m + 1, I0{}, IH{});
+        // finish worker m (packed tile in `raw`); with PREFETCH worker m + 1 is requested into `nraw` meanwhile
+        auto process = [&](uint32_t (&raw)[kSP], uint32_t (&nraw)[kSP], uint32_t m, auto prefetch) {
+            constexpr bool PREFETCH = decltype(prefetch)::value;
+            if constexpr (PREFETCH) request(nraw, m + 1);
             const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
             __syncthreads(); // the previous worker's eps words and exchange buffer are no longer read
-            fill_eps<T>(epsw, g, key_eps, t);
-            stages_a<int32_t, LV>(buf, cb);
-            if (more) request(nbuf, m + 1, IH{}, IV{});
+            fill_eps(epsw, g, key_eps, t);
+            int32_t buf[kSV];
+#pragma unroll
+            for (int p = 0; p < kSP; ++p) {
+                buf[2 * p] = (int32_t)(int16_t)(raw[p] & 0xFFFFu);
+                buf[2 * p + 1] = (int32_t)raw[p] >> 16;
+            }
+            stages_a<int32_t>(buf, cb);
             if (need_x) {
-                exchange<int32_t, LV>(buf, xbuf, lane, wave);
-                stages_b<int32_t, LV>(buf, cb);
+                exchange<int32_t>(buf, xbuf, lane, wave);
+                stages_b<int32_t>(buf, cb);
             } else {
                 __syncthreads();
             }
             const float c = a.scales[(uint64_t)m * a.scales_stride + gb] * a.out_coef;
 #pragma unroll
-            for (int r = 0; r < V; ++r)
-                acc[r] += flip_if(c * (float)buf[r], (epsw[(ut_out >> 5) + (ureg_out(r) >> 5)] >> ebit) & 1u);
+            for (int p = 0; p < kSP; ++p) {
+                float y0 = c * (float)buf[2 * p], y1 = c * (float)buf[2 * p + 1];
+                flip_pair(y0, y1, epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
+                acc[2 * p] += y0;
+                acc[2 * p + 1] += y1;
+            }
         };
-        request(bufa, 0, I0{}, IV{});
-        for (uint32_t m = 0; m < a.M; m += 2) {
-            // keep the per-register row offsets (functions of ls) from being hoisted out of this loop
-            // and held in scalar registers for its whole duration
-            if constexpr (HB == 0) asm volatile("" : "+s"(g.ls));
-            process(bufa, bufb, m);
-            if (m + 1 < a.M) process(bufb, bufa, m + 1);
+        if constexpr (HB != 0) {
+            request(rawa, 0);
+            uint32_t m = 0;
+            for (; m + 2 < a.M; m += 2) {
+                process(rawa, rawb, m, std::true_type{});
+                process(rawb, rawa, m + 1, std::true_type{});
+            }
+            if (m + 1 < a.M) { // two workers left
+                process(rawa, rawb, m, std::true_type{});
+                process(rawb, rawa, m + 1, std::false_type{});
+            } else {           // one worker left
+                process(rawa, rawb, m, std::false_type{});
+            }
+        } else {
+            // generic geometry: no prefetch (the per-register offsets are not constants here and holding
+            // them across iterations costs more registers than the overlap is worth)
+            for (uint32_t m = 0; m < a.M; ++m) {
+                asm volatile("" : "+s"(g.ls));
+                request(rawa, m);
+                process(rawa, rawb, m, std::false_type{});
+            }
         }
         if (a.gbar) {
             float *gq = a.gbar + g.origin;
 #pragma unroll
-            for (int r = 0; r < V; ++r) ref_at(gq + g.off(ureg_out(r)), ob_out) = acc[r];
+            for (int p = 0; p < kSP; ++p)
+                ref_at<float2>(gq + g.off(upair_out(p)), ot_out * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
         }
         // re-encode: eps^s flip, then the same stages in reverse layout order
         const RngKey key_s = { a.k0, a.k1, kDomainEps, a.round_lo, a.eps_party0 };
         __syncthreads();
-        fill_eps<T>(epsw, g, key_s, t);
+        fill_eps(epsw, g, key_s, t);
         __syncthreads();
 #pragma unroll
-        for (int r = 0; r < V; ++r)
-            acc[r] = flip_if(acc[r], (epsw[(ut_out >> 5) + (ureg_out(r) >> 5)] >> ebit) & 1u);
+        for (int p = 0; p < kSP; ++p)
+            flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
         if (need_x) {
-            stages_b<float, LV>(acc, cb);
-            exchange<float, LV>(acc, xbuf, lane, wave);
+            stages_b<float>(acc, cb);
+            exchange<float>(acc, xbuf, lane, wave);
         }
-        stages_a<float, LV>(acc, cb);
+        stages_a<float>(acc, cb);
         float *dst = static_cast<float *>(a.dst) + g.origin;
 #pragma unroll
-        for (int r = 0; r < V; ++r) ref_at(dst + g.off(L::ra(r)), oba) = acc[r];
+        for (int p = 0; p < kSP; ++p)
+            ref_at<float2>(dst + g.off(sa_pair(p)), ota * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
     }
 }
 
