@@ -322,27 +322,28 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
         // ==================================================================== server
         static_assert(IN16, "the server pass reads the int16 intermediate");
         float acc[kSV];
-        uint32_t rawa[kSP], rawb[kSP]; // ping-pong of packed tiles: one is transformed while the next one travels
+        uint32_t raw[kSP]; // packed tile of the next worker, in flight while the current one is transformed
 #pragma unroll
         for (int r = 0; r < kSV; ++r) acc[r] = 0.f;
-        auto request = [&](uint32_t (&raw)[kSP], uint32_t m) {
+        auto request = [&](uint32_t m) {
             const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin;
 #pragma unroll
             for (int p = 0; p < kSP; ++p) raw[p] = ld_at<uint32_t>(src + g.off(sa_pair(p)), ota * 2u);
         };
-        // finish worker m (packed tile in `raw`); with PREFETCH worker m + 1 is requested into `nraw` meanwhile
-        auto process = [&](uint32_t (&raw)[kSP], uint32_t (&nraw)[kSP], uint32_t m, auto prefetch) {
+        // finish worker m, whose packed tile is in `raw`; with PREFETCH the registers of `raw` are refilled
+        // with worker m + 1 as soon as they have been unpacked
+        auto process = [&](uint32_t m, auto prefetch) {
             constexpr bool PREFETCH = decltype(prefetch)::value;
-            if constexpr (PREFETCH) request(nraw, m + 1);
-            const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
-            __syncthreads(); // the previous worker's eps words and exchange buffer are no longer read
-            fill_eps(epsw, g, key_eps, t);
             int32_t buf[kSV];
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
                 buf[2 * p] = (int32_t)(int16_t)(raw[p] & 0xFFFFu);
                 buf[2 * p + 1] = (int32_t)raw[p] >> 16;
             }
+            if constexpr (PREFETCH) request(m + 1);
+            const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
+            __syncthreads(); // the previous worker's eps words and exchange buffer are no longer read
+            fill_eps(epsw, g, key_eps, t);
             stages_a<int32_t>(buf, cb);
             if (need_x) {
                 exchange<int32_t>(buf, xbuf, lane, wave);
@@ -359,28 +360,14 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
                 acc[2 * p + 1] += y1;
             }
         };
-        if constexpr (HB != 0) {
-            request(rawa, 0);
-            uint32_t m = 0;
-            for (; m + 2 < a.M; m += 2) {
-                process(rawa, rawb, m, std::true_type{});
-                process(rawb, rawa, m + 1, std::true_type{});
-            }
-            if (m + 1 < a.M) { // two workers left
-                process(rawa, rawb, m, std::true_type{});
-                process(rawb, rawa, m + 1, std::false_type{});
-            } else {           // one worker left
-                process(rawa, rawb, m, std::false_type{});
-            }
-        } else {
-            // generic geometry: no prefetch (the per-register offsets are not constants here and holding
-            // them across iterations costs more registers than the overlap is worth)
-            for (uint32_t m = 0; m < a.M; ++m) {
-                asm volatile("" : "+s"(g.ls));
-                request(rawa, m);
-                process(rawa, rawb, m, std::false_type{});
-            }
+        request(0);
+        for (uint32_t m = 0; m + 1 < a.M; ++m) {
+            // generic geometry: keep the per-register row offsets (functions of ls) from being hoisted out of
+            // this loop and held in scalar registers for its whole duration
+            if constexpr (HB == 0) asm volatile("" : "+s"(g.ls));
+            process(m, std::true_type{});
         }
+        process(a.M - 1, std::false_type{});
         if (a.gbar) {
             float *gq = a.gbar + g.origin;
 #pragma unroll
