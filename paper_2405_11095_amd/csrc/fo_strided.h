@@ -58,17 +58,27 @@ struct StridedGeom {
     }
 };
 
-constexpr int kSV = 64;        // values per thread
-constexpr int kSP = kSV / 2;   // pairs per thread
-
-// thread part and (wave-uniform) pair part of a tile coordinate; p = register number >> 1
-__device__ __forceinline__ uint32_t sa_thread(uint32_t lane, uint32_t wave) { return (lane << 1) | (wave << 7); }
-__device__ __forceinline__ constexpr uint32_t sa_pair(int p) { return (uint32_t)p << 10; }
-__device__ __forceinline__ uint32_t sb_thread(uint32_t lane, uint32_t wave) { return (lane << 1) | (wave << 10); }
-__device__ __forceinline__ constexpr uint32_t sb_pair(int p)
-{
-    return ((uint32_t)(p & 7) << 7) | ((uint32_t)(p >> 3) << 13);
-}
+// Layout constants for V = 2^LV values per thread (as V/2 pairs) and 2^(15-LV) threads.
+//   LA: reg0 = u0, lanes = (u1..u6), waves = (u7..u6+NW), register bits 1.. = (u7+NW..u14)
+//   LB: reg0 = u0, lanes = (u1..u6), waves = (u7+NW..u6+2NW), register bits 1..NW = (u7..u6+NW),
+//       register bits above NW unchanged
+template <int LV>
+struct SL {
+    static constexpr int V = 1 << LV;       // values per thread
+    static constexpr int P = V / 2;         // pairs per thread
+    static constexpr int T = (int)kTile >> LV;
+    static constexpr int NW = 9 - LV;       // wave bits: 3 for V = 64, 4 for V = 32
+    static constexpr int NR = LV - 1;       // register bits other than the pair bit
+    static_assert(NR >= NW, "the exchange needs as many register bits as wave bits");
+    // thread part and (wave-uniform) pair part of a tile coordinate; p = register number >> 1
+    static __device__ __forceinline__ uint32_t ta(uint32_t lane, uint32_t wave) { return (lane << 1) | (wave << 7); }
+    static __device__ __forceinline__ constexpr uint32_t pa(int p) { return (uint32_t)p << (7 + NW); }
+    static __device__ __forceinline__ uint32_t tb(uint32_t lane, uint32_t wave) { return (lane << 1) | (wave << (7 + NW)); }
+    static __device__ __forceinline__ constexpr uint32_t pb(int p)
+    {
+        return ((uint32_t)(p & ((1 << NW) - 1)) << 7) | ((uint32_t)(p >> NW) << (7 + 2 * NW));
+    }
+};
 
 // Access through a wave-uniform base pointer plus a 32-bit per-lane byte offset.
 template <typename T>
@@ -83,11 +93,12 @@ __device__ __forceinline__ T &ref_at(void *uniform_base, uint32_t byte_off)
 }
 
 // eps words of the tile, one 32-bit word per group of 32 consecutive columns (u >> 5)
+template <int T>
 __device__ __forceinline__ void fill_eps(uint32_t *epsw, const StridedGeom &g, const RngKey &key, uint32_t t)
 {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-        const uint32_t grp = t + h * kThreads;
+    for (int h = 0; h < 1024 / T; ++h) {
+        const uint32_t grp = t + h * T;
         const uint64_t i = g.origin + g.off(grp << 5);
         uint32_t w[4];
         philox((uint32_t)(i >> 7), key, w);
@@ -114,49 +125,54 @@ __device__ __forceinline__ void bfly_lane4(T (&v)[V])
     }
 }
 
-// stages on lane bits 4, 5 (u5, u6) and on register bits 1..5 of LA (u10..u14)
-template <typename T>
-__device__ __forceinline__ void stages_a(T (&v)[kSV], uint32_t cb)
+// stages on lane bits 4, 5 (u5, u6) and on the register bits of LA (register bit k <-> u bit 6 + NW + k)
+template <typename T, int LV>
+__device__ __forceinline__ void stages_a(T (&v)[1 << LV], uint32_t cb)
 {
-    if (cb <= 5u) bfly_lane4<T, kSV>(v);
-    if (cb <= 6u) bfly_lane5<T, kSV>(v);
-    if (cb <= 10u) bfly<T, 1, kSV>(v);
-    if (cb <= 11u) bfly<T, 2, kSV>(v);
-    if (cb <= 12u) bfly<T, 3, kSV>(v);
-    if (cb <= 13u) bfly<T, 4, kSV>(v);
-    bfly<T, 5, kSV>(v);
+    constexpr int V = 1 << LV, B1 = 7 + SL<LV>::NW; // u bit of register bit 1
+    if (cb <= 5u) bfly_lane4<T, V>(v);
+    if (cb <= 6u) bfly_lane5<T, V>(v);
+    if (cb <= (uint32_t)B1) bfly<T, 1, V>(v);
+    if (cb <= (uint32_t)B1 + 1) bfly<T, 2, V>(v);
+    if (cb <= (uint32_t)B1 + 2) bfly<T, 3, V>(v);
+    if (cb <= (uint32_t)B1 + 3) bfly<T, 4, V>(v);
+    if constexpr (LV > 5) {
+        if (cb <= (uint32_t)B1 + 4) bfly<T, 5, V>(v);
+    }
 }
-// stages on register bits 1..3 of LB (u7, u8, u9)
-template <typename T>
-__device__ __forceinline__ void stages_b(T (&v)[kSV], uint32_t cb)
+// stages on register bits 1..NW of LB (u7 ..)
+template <typename T, int LV>
+__device__ __forceinline__ void stages_b(T (&v)[1 << LV], uint32_t cb)
 {
-    if (cb <= 7u) bfly<T, 1, kSV>(v);
-    if (cb <= 8u) bfly<T, 2, kSV>(v);
-    if (cb <= 9u) bfly<T, 3, kSV>(v);
+    constexpr int V = 1 << LV;
+    if (cb <= 7u) bfly<T, 1, V>(v);
+    if (cb <= 8u) bfly<T, 2, V>(v);
+    if (cb <= 9u) bfly<T, 3, V>(v);
+    if constexpr (SL<LV>::NW > 3) {
+        if (cb <= 10u) bfly<T, 4, V>(v);
+    }
 }
 
-// LA <-> LB through LDS in two halves split on register bit 5 (a spectator): the wave index and
-// register bits 1..3 trade places (the map is its own inverse).  A lane moves a pair (8 bytes).
-// Word address: u0 | lane << 1 | wave-bits << 7 | register-bits-1..3 << 10 | register-bit-4 << 13.
-template <typename T>
-__device__ __forceinline__ void exchange(T (&v)[kSV], uint32_t *xbuf, uint32_t lane, uint32_t wave)
+// LA <-> LB through LDS: the wave index and register bits 1..NW trade places (the map is its own
+// inverse).  Two halves, one per member of the pairs, so a lane moves 4 bytes per access and the
+// lanes of a wave hit consecutive words.
+// Word address: lane | wave-bits << 6 | register-bits-1..NW << (6 + NW) | higher register bits << (6 + 2 NW).
+template <typename T, int LV>
+__device__ __forceinline__ void exchange(T (&v)[1 << LV], uint32_t *xbuf, uint32_t lane, uint32_t wave)
 {
-    uint2 *const wp = reinterpret_cast<uint2 *>(xbuf) + (lane | (wave << 6));
-    uint2 *const rp = reinterpret_cast<uint2 *>(xbuf) + (lane | (wave << 9));
+    constexpr int P = SL<LV>::P, NW = SL<LV>::NW;
+    uint32_t *const wp = xbuf + (lane | (wave << 6));
+    uint32_t *const rp = xbuf + (lane | (wave << (6 + NW)));
 #pragma unroll
     for (int sub = 0; sub < 2; ++sub) {
         if (sub) __syncthreads();
 #pragma unroll
-        for (int p = 0; p < 16; ++p) // pair p of this half: register bits 1..3 = p & 7, bit 4 = p >> 3
-            wp[((p & 7) << 9) | ((p >> 3) << 12)] =
-                make_uint2(__builtin_bit_cast(uint32_t, v[sub * 32 + 2 * p]), __builtin_bit_cast(uint32_t, v[sub * 32 + 2 * p + 1]));
+        for (int p = 0; p < P; ++p)
+            wp[((p & ((1 << NW) - 1)) << (6 + NW)) | ((p >> NW) << (6 + 2 * NW))] = __builtin_bit_cast(uint32_t, v[2 * p + sub]);
         __syncthreads();
 #pragma unroll
-        for (int p = 0; p < 16; ++p) {
-            const uint2 d = rp[((p & 7) << 6) | ((p >> 3) << 12)];
-            v[sub * 32 + 2 * p] = __builtin_bit_cast(T, d.x);
-            v[sub * 32 + 2 * p + 1] = __builtin_bit_cast(T, d.y);
-        }
+        for (int p = 0; p < P; ++p)
+            v[2 * p + sub] = __builtin_bit_cast(T, rp[((p & ((1 << NW) - 1)) << 6) | ((p >> NW) << (6 + 2 * NW))]);
     }
 }
 
@@ -171,9 +187,13 @@ __device__ __forceinline__ void flip_pair(float &x0, float &x1, uint32_t wshift)
 // for exactly HB stages with rows 2^15 apart (the pass next to the contiguous tile), which turns
 // every per-register offset into a constant and removes the stage-selection branches.
 // IN16: the integer input is the contiguous kernel's int16 intermediate.
-template <int MODE, int HB, bool IN16>
-__global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strided(const StridedArgs a, const PtrTab tab)
+// LV: log2 of the values per thread (6: 512 threads; 5: 1024 threads, used where two tiles' worth of
+// registers per thread are needed and more waves hide latency better).
+template <int MODE, int HB, bool IN16, int LV>
+__global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, const PtrTab tab)
 {
+    using L = SL<LV>;
+    constexpr int kSV = L::V, kSP = L::P;
     constexpr bool FIN = (MODE == SM_ENC_FIRST || MODE == SM_MID_F32); // fp32 input
     using TV = typename std::conditional<FIN, float, int32_t>::type;
     __shared__ uint32_t lds[kLdsWords];
@@ -189,7 +209,7 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
     // they are given block indices that land on the same XCD (blocks are dealt round-robin over 8 XCDs)
     uint32_t tile = blockIdx.x;
     if (IN16 && cb == 5u) tile = (tile & ~15u) | ((tile & 7u) << 1) | ((tile >> 3) & 1u);
-    const bool need_x = cb <= 9u; // some row bit lives in the wave index
+    const bool need_x = cb <= 6u + (uint32_t)L::NW; // some row bit lives in the wave index
     StridedGeom g;
     g.cb = cb;
     g.ls = HB ? (uint32_t)kTileLog2 : a.ls;
@@ -201,18 +221,18 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
     const uint64_t gb = g.origin >> a.logb; // the tile lies inside one block
 
     // thread parts of the tile coordinate and of the element offset in both layouts
-    const uint32_t uta = sa_thread(lane, wave), utb = sb_thread(lane, wave);
+    const uint32_t uta = L::ta(lane, wave), utb = L::tb(lane, wave);
     const uint32_t ota = g.off(uta), otb = g.off(utb);
     // layout in which the transformed tile is held: LB if the exchange ran, else LA
     const uint32_t ut_out = need_x ? utb : uta, ot_out = need_x ? otb : ota;
-    auto upair_out = [&](int p) -> uint32_t { return need_x ? sb_pair(p) : sa_pair(p); };
+    auto upair_out = [&](int p) -> uint32_t { return need_x ? L::pb(p) : L::pa(p); };
     const uint32_t eshift = (lane & 15u) << 1; // bit of column u0 = 0 inside its eps word
 
     // ---- input of one tile (layout LA) as 32 pairs
     auto load_int = [&](int32_t (&v)[kSV], const void *src_base) {
 #pragma unroll
         for (int p = 0; p < kSP; ++p) {
-            const uint32_t ro = g.off(sa_pair(p)); // wave-uniform
+            const uint32_t ro = g.off(L::pa(p)); // wave-uniform
             if constexpr (IN16) {
                 const uint32_t d = ld_at<uint32_t>(static_cast<const int16_t *>(src_base) + ro, ota * 2u);
                 v[2 * p] = (int32_t)(int16_t)(d & 0xFFFFu);
@@ -229,7 +249,7 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
         TV v[kSV];
         const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
         const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
-        if constexpr (MODE == SM_ENC_FIRST || MODE == SM_DEC_LAST) fill_eps(epsw, g, key_eps, t);
+        if constexpr (MODE == SM_ENC_FIRST || MODE == SM_DEC_LAST) fill_eps<L::T>(epsw, g, key_eps, t);
 
         // ---------------------------------------------------------------- load (LA)
         if constexpr (MODE == SM_ENC_FIRST) {
@@ -238,7 +258,7 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
             src += g.origin;
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
-                const uint32_t ro = g.off(sa_pair(p)); // wave-uniform
+                const uint32_t ro = g.off(L::pa(p)); // wave-uniform
                 const uint64_t e = (uint64_t)ro + ota;
                 float2 d = make_float2(0.f, 0.f);
                 if (e + 1 < room) d = ld_at<float2>(src + ro, ota * 4u);
@@ -255,17 +275,17 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
             __syncthreads(); // also publishes epsw
             if (t == 0) {
                 float s = 0.f;
-                for (int w = 0; w < kThreads / 64; ++w) s += red[w];
+                for (int w = 0; w < L::T / 64; ++w) s += red[w];
                 a.partials[(uint64_t)slot * gridDim.x + tile] = s;
             }
 #pragma unroll
             for (int p = 0; p < kSP; ++p)
-                flip_pair(v[2 * p], v[2 * p + 1], epsw[(uta >> 5) + (sa_pair(p) >> 5)] >> eshift);
+                flip_pair(v[2 * p], v[2 * p + 1], epsw[(uta >> 5) + (L::pa(p) >> 5)] >> eshift);
         } else if constexpr (MODE == SM_MID_F32) {
             const float *src = static_cast<const float *>(a.src) + slot * a.src_stride + g.origin;
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
-                const float2 d = ld_at<float2>(src + g.off(sa_pair(p)), ota * 4u);
+                const float2 d = ld_at<float2>(src + g.off(L::pa(p)), ota * 4u);
                 v[2 * p] = d.x;
                 v[2 * p + 1] = d.y;
             }
@@ -275,10 +295,10 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
         }
 
         // ---------------------------------------------------------------- stages
-        stages_a<TV>(v, cb);
+        stages_a<TV, LV>(v, cb);
         if (need_x) {
-            exchange<TV>(v, xbuf, lane, wave);
-            stages_b<TV>(v, cb);
+            exchange<TV, LV>(v, xbuf, lane, wave);
+            stages_b<TV, LV>(v, cb);
         } else if (MODE == SM_DEC_LAST) {
             __syncthreads(); // publishes epsw
         }
@@ -328,7 +348,7 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
         auto request = [&](uint32_t m) {
             const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin;
 #pragma unroll
-            for (int p = 0; p < kSP; ++p) raw[p] = ld_at<uint32_t>(src + g.off(sa_pair(p)), ota * 2u);
+            for (int p = 0; p < kSP; ++p) raw[p] = ld_at<uint32_t>(src + g.off(L::pa(p)), ota * 2u);
         };
         // finish worker m, whose packed tile is in `raw`; with PREFETCH the registers of `raw` are refilled
         // with worker m + 1 as soon as they have been unpacked
@@ -343,11 +363,11 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
             if constexpr (PREFETCH) request(m + 1);
             const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
             __syncthreads(); // the previous worker's eps words and exchange buffer are no longer read
-            fill_eps(epsw, g, key_eps, t);
-            stages_a<int32_t>(buf, cb);
+            fill_eps<L::T>(epsw, g, key_eps, t);
+            stages_a<int32_t, LV>(buf, cb);
             if (need_x) {
-                exchange<int32_t>(buf, xbuf, lane, wave);
-                stages_b<int32_t>(buf, cb);
+                exchange<int32_t, LV>(buf, xbuf, lane, wave);
+                stages_b<int32_t, LV>(buf, cb);
             } else {
                 __syncthreads();
             }
@@ -377,20 +397,20 @@ __global__ __launch_bounds__(kThreads, (MODE == SM_SERVER ? 2 : 4)) void k_strid
         // re-encode: eps^s flip, then the same stages in reverse layout order
         const RngKey key_s = { a.k0, a.k1, kDomainEps, a.round_lo, a.eps_party0 };
         __syncthreads();
-        fill_eps(epsw, g, key_s, t);
+        fill_eps<L::T>(epsw, g, key_s, t);
         __syncthreads();
 #pragma unroll
         for (int p = 0; p < kSP; ++p)
             flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
         if (need_x) {
-            stages_b<float>(acc, cb);
-            exchange<float>(acc, xbuf, lane, wave);
+            stages_b<float, LV>(acc, cb);
+            exchange<float, LV>(acc, xbuf, lane, wave);
         }
-        stages_a<float>(acc, cb);
+        stages_a<float, LV>(acc, cb);
         float *dst = static_cast<float *>(a.dst) + g.origin;
 #pragma unroll
         for (int p = 0; p < kSP; ++p)
-            ref_at<float2>(dst + g.off(sa_pair(p)), ota * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
+            ref_at<float2>(dst + g.off(L::pa(p)), ota * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
     }
 }
 
