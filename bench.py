@@ -80,7 +80,7 @@ def main():
     per_step = {
         "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
         "k_contig<IN_F32,OUT_PACK>": (M + 1) * (4 * n + W8),
-        "k_contig<IN_BITS,OUT_I32>": (M + 1) * (W8 + 4 * n),
+        "k_contig<IN_BITS,OUT_I16>": (M + 1) * (W8 + 4 * n),
         "k_strided<SERVER>": M * 4 * n + 4 * n,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),

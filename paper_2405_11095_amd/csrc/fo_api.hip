@@ -76,7 +76,7 @@ enum KernelId {
     KID_ENC_MID,        // k_strided<MID_F32>
     KID_ENC_LOW,        // k_contig<IN_F32,OUT_PACK>
     KID_DEC_SINGLE,     // k_contig<IN_BITS,OUT_F32>
-    KID_DEC_LOW,        // k_contig<IN_BITS,OUT_I32>
+    KID_DEC_LOW,        // k_contig<IN_BITS,OUT_I16> (OUT_I32 for three-pass transforms)
     KID_DEC_MID,        // k_strided<MID_I32>
     KID_DEC_HIGH,       // k_strided<DEC_LAST>
     KID_SERVER_HIGH,    // k_strided<SERVER>
@@ -85,7 +85,7 @@ enum KernelId {
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
-    "k_contig<IN_BITS,OUT_F32>",  "k_contig<IN_BITS,OUT_I32>", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
+    "k_contig<IN_BITS,OUT_F32>",  "k_contig<IN_BITS,OUT_I16>", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
     "k_strided<SERVER>", "scale kernels",
 };
 

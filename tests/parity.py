@@ -144,3 +144,66 @@ def gates(rep, tol=1e-5):
     if "x_rel_l2" in rep:
         assert rep["step_messages_equal"], rep
         assert rep["x_rel_l2"] <= tol, rep
+
+
+def check_sampled_blocks(O, B, gs, d, M, block_log2, seed, rnd, device, block_ranges, threads=8):
+    """Full-size blocked workloads: the GPU runs the whole round through fo_step; the oracle checks
+    the stages on sampled ranges of blocks only (blocks are independent transforms), teacher-forced
+    as in check_round_trip.  block_ranges: list of (j0, nj)."""
+    import torch
+
+    plan = B.Plan(d=d, M=M, block_log2=block_log2, seed=seed)
+    p = O.params(d=d, M=M, block_log2=block_log2, seed=seed)
+    b, nb, nt = O.geometry(p)
+    W = nt // 64
+    gd = [torch.from_numpy(g).to(device) for g in gs]
+    x0 = np.zeros(d, dtype=np.float32)
+    x = torch.from_numpy(x0.copy()).to(device)
+    delta = 1.0                                  # x becomes minus the decoded downlink vector
+    plan.fo_step(gd, x, delta, rnd)
+    torch.cuda.synchronize()
+    pb_up, ps_up, pb_dn, ps_dn = plan.fo_step_messages()
+    bits_up = _peek(torch, pb_up, M * W, torch.int64, device).view(np.uint64).reshape(M, W)
+    lam_up = _peek(torch, ps_up, M * nb, torch.float32, device).reshape(M, nb)
+    bits_dn = _peek(torch, pb_dn, W, torch.int64, device).view(np.uint64)
+    lam_s = _peek(torch, ps_dn, nb, torch.float32, device)
+    hx = x.cpu().numpy()
+    del gd, x
+    rep = dict(d=d, M=M, b=b, nblocks=nb, blocks_checked=0, uplink_mismatch=0, uplink_exempt=0, lam_rel_err=0.0,
+               lam_s_rel_err=0.0, downlink_mismatch=0, downlink_exempt=0, decode_rel_l2=0.0)
+    ps = O.params(d=nt, M=M, block_log2=block_log2, seed=seed)   # the server encodes a vector of length ntot
+    for (j0, nj) in block_ranges:
+        lo, hi = j0 * b, min(d, (j0 + nj) * b)
+        wlo, whi = j0 * b // 64, (j0 + nj) * b // 64
+
+        def uplink(m):
+            xs = gs[m][lo:hi].astype(np.float64)
+            free = O.encode_blocks(p, xs, rnd, m, j0, nj)["lam"]
+            r = O.encode_blocks(p, xs, rnd, m, j0, nj, lam=lam_up[m, j0:j0 + nj].astype(np.float64), want_margin=True)
+            bad, exempt, _ = compare_bits(bits_up[m, wlo:whi], r["margin"], lam_up[m, j0:j0 + nj], b)
+            den = np.where(free > 0, free, 1.0)
+            return bad, exempt, float(np.max(np.abs(lam_up[m, j0:j0 + nj] - free) / den))
+
+        with ThreadPoolExecutor(max_workers=threads) as ex:
+            res = list(ex.map(uplink, range(M)))
+        rep["uplink_mismatch"] += sum(r[0] for r in res)
+        rep["uplink_exempt"] += sum(r[1] for r in res)
+        rep["lam_rel_err"] = max(rep["lam_rel_err"], max(r[2] for r in res))
+        # server on the sampled blocks: decode every worker's GPU bits, average, re-encode
+        gbar = np.zeros(nj * b)
+        for m in range(M):
+            q = O.unpack(bits_up[m, wlo:whi], nj * b)
+            gbar += O.decode_blocks(p, q, lam_up[m, j0:j0 + nj].astype(np.float64), rnd, m, j0, nj)
+        gbar /= M
+        free_s = 2.0 * lam_up[:, j0:j0 + nj].astype(np.float64).max(axis=0) * np.sqrt(np.log(b))
+        den = np.where(free_s > 0, free_s, 1.0)
+        rep["lam_s_rel_err"] = max(rep["lam_s_rel_err"], float(np.max(np.abs(lam_s[j0:j0 + nj] - free_s) / den)))
+        r = O.encode_blocks(ps, gbar, rnd, SERVER, j0, nj, lam=lam_s[j0:j0 + nj].astype(np.float64), want_margin=True)
+        bad, exempt, _ = compare_bits(bits_dn[wlo:whi], r["margin"], lam_s[j0:j0 + nj], b)
+        rep["downlink_mismatch"] += bad
+        rep["downlink_exempt"] += exempt
+        dec = O.decode_blocks(p, O.unpack(bits_dn[wlo:whi], nj * b), lam_s[j0:j0 + nj].astype(np.float64), rnd, SERVER, j0, nj)
+        rep["decode_rel_l2"] = max(rep["decode_rel_l2"], rel_l2(-hx[lo:hi].astype(np.float64), dec[:hi - lo]))
+        rep["blocks_checked"] += nj
+    plan.close()
+    return rep

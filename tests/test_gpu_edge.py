@@ -1,0 +1,177 @@
+"""GPU edge cases and full-size workloads, through the C ABI, against the CPU oracle."""
+import numpy as np
+import pytest
+
+from tests.parity import SERVER, check_round_trip, check_sampled_blocks, gates
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    from paper_2405_11095_amd import binding, inputs
+    assert torch.cuda.is_available()
+    binding.load_library()
+    return oracle, binding, inputs, torch.device("cuda:0")
+
+
+def _encode(B, torch, dev, plan, g, rnd, party, flags=0, scales=None):
+    bits = torch.zeros(plan.W, dtype=torch.int64, device=dev)
+    lam = torch.zeros(plan.nblocks, dtype=torch.float32, device=dev) if scales is None else scales
+    plan.fo_encode(torch.from_numpy(g).to(dev), rnd, party, bits, lam, flags)
+    torch.cuda.synchronize()
+    return bits, lam
+
+
+@pytest.mark.parametrize("d,blk", [(1000, 0), (70_000, 0), (5000, 7)])
+def test_zero_gradient(env, d, blk):
+    """sign(0) = +1: every bit is set, lambda = 0, the decoded vector and the update are exactly 0."""
+    import torch
+    O, B, inputs, dev = env
+    plan = B.Plan(d=d, M=2, block_log2=blk, seed=9)
+    g = np.zeros(d, dtype=np.float32)
+    g[1::2] = -0.0
+    bits, lam = _encode(B, torch, dev, plan, g, 3, 0)
+    assert torch.all(lam == 0)
+    assert np.all(bits.cpu().numpy().view(np.uint64) == np.uint64(0xFFFFFFFFFFFFFFFF))
+    out = torch.full((d,), 7.0, dtype=torch.float32, device=dev)
+    plan.fo_decode(bits, lam, 3, 0, out)
+    x = torch.ones(d, dtype=torch.float32, device=dev)
+    gz = torch.from_numpy(g).to(dev)
+    plan.fo_step([gz, gz], x, 0.5, 3)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0) and torch.all(x == 1)
+
+
+def test_nan_input_is_defined(env):
+    """A NaN entry makes the norm, hence lambda, NaN: every comparison is false (all bits 0) and the
+    decoded vector is NaN; nothing faults."""
+    import torch
+    O, B, inputs, dev = env
+    d = 4096
+    plan = B.Plan(d=d, M=1, seed=1)
+    g = inputs.gaussian(d, 0)
+    g[17] = np.nan
+    bits, lam = _encode(B, torch, dev, plan, g, 0, 0)
+    assert torch.isnan(lam).all()
+    assert np.all(bits.cpu().numpy() == 0)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan.fo_decode(bits, lam, 0, 0, out)
+    torch.cuda.synchronize()
+    assert torch.isnan(out).all()
+
+
+def test_determinism_and_seed_sensitivity(env):
+    import torch
+    O, B, inputs, dev = env
+    d = 100_000
+    g = inputs.heavy_tailed(d, 0)
+    p1, p2, p3 = B.Plan(d=d, M=1, seed=5), B.Plan(d=d, M=1, seed=5), B.Plan(d=d, M=1, seed=6)
+    b1, l1 = _encode(B, torch, dev, p1, g, 4, 0)
+    b2, l2 = _encode(B, torch, dev, p2, g, 4, 0)
+    b3, _ = _encode(B, torch, dev, p3, g, 4, 0)
+    b4, _ = _encode(B, torch, dev, p1, g, 5, 0)
+    assert torch.equal(b1, b2) and torch.equal(l1, l2)
+    for other in (b3, b4):
+        diff = (b1 ^ other).cpu().numpy().view(np.uint64)
+        frac = sum(bin(int(w)).count("1") for w in diff[:2000]) / (2000 * 64)
+        assert 0.3 < frac < 0.7
+
+
+@pytest.mark.parametrize("name,kw", [
+    ("bound_rule", dict(scale_rule=0, Bnorm=400.0)),
+    ("no_dither", dict(dither=1)),
+    ("alpha3", dict(alpha=3.0, alpha_s=2.5)),
+])
+def test_parameter_variants(env, name, kw):
+    O, B, inputs, dev = env
+    d, M = 150_000, 3
+    gs = [inputs.gaussian(d, m) for m in range(M)]
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=0, seed=77, rnd=2, delta=0.1, device=dev, **kw)
+    print(name, rep, flush=True)
+    gates(rep)
+
+
+def test_forced_scale_is_used(env):
+    import torch
+    O, B, inputs, dev = env
+    d = 50_000
+    plan = B.Plan(d=d, M=1, seed=3)
+    g = inputs.gaussian(d, 0)
+    forced = torch.full((1,), 0.123, dtype=torch.float32, device=dev)
+    bits, lam = _encode(B, torch, dev, plan, g, 1, 0, flags=B.FORCE_SCALE, scales=forced)
+    assert float(lam[0]) == np.float32(0.123)
+    p = O.params(d=d, M=1, seed=3)
+    r = O.encode(p, g.astype(np.float64), 1, 0, lam=np.array([float(np.float32(0.123))]), want_margin=True)
+    from tests.parity import compare_bits
+    bad, exempt, _ = compare_bits(bits.cpu().numpy().view(np.uint64), r["margin"], [0.123], plan.b)
+    assert bad == 0
+
+
+def test_argument_errors(env):
+    import torch
+    O, B, inputs, dev = env
+    plan = B.Plan(d=1000, M=2, seed=1)
+    g = torch.zeros(1004, dtype=torch.float32, device=dev)
+    bits = torch.zeros(plan.W, dtype=torch.int64, device=dev)
+    lam = torch.zeros(1, dtype=torch.float32, device=dev)
+    with pytest.raises(B.FoError) as e:
+        plan.fo_encode(g, 0, 2, bits, lam)            # party out of range
+    assert e.value.code == B.EINVAL
+    with pytest.raises(B.FoError) as e:
+        plan.fo_encode(g[1:], 0, 0, bits, lam)        # gradient not 16-byte aligned
+    assert e.value.code == B.EALIGN
+    with pytest.raises(B.FoError) as e:
+        plan.fo_encode(g, 0, 0, bits, lam, flags=8)   # unknown flag
+    assert e.value.code == B.EINVAL
+
+
+def test_single_worker_and_odd_worker_counts(env):
+    O, B, inputs, dev = env
+    for M in (1, 5):
+        d = (1 << 20) + 3
+        gs = [inputs.gaussian(d, m) for m in range(M)]
+        rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=0, seed=31 + M, rnd=9, delta=0.1, device=dev)
+        print(M, rep, flush=True)
+        gates(rep)
+
+
+def test_three_pass_transform(env):
+    """n = 2^26: two strided passes around the contiguous one."""
+    O, B, inputs, dev = env
+    d, M = (1 << 26) - 12345, 1
+    gs = [inputs.gaussian(d, 0)]
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=0, seed=5, rnd=1, delta=0.1, device=dev)
+    print(rep, flush=True)
+    gates(rep)
+
+
+def test_c2_sparse_workload(env):
+    """1 % dense gradients are flattened: no coordinate of H_eps g exceeds lambda (event A of Thm 5.5)."""
+    O, B, inputs, dev = env
+    d, M = 1 << 20, 8
+    gs = inputs.workload("c2")
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=0, seed=0xF05D + 2, rnd=0, delta=0.01, device=dev)
+    print(rep, flush=True)
+    gates(rep)
+    p = O.params(d=d, M=M, seed=0xF05D + 2)
+    r = O.encode(p, gs[0].astype(np.float64), 0, 0, want_z=True)
+    assert np.max(np.abs(r["z"])) <= r["lam"][0]
+    assert np.max(np.abs(gs[0])) / np.sqrt(np.mean(gs[0].astype(np.float64) ** 2)) > 5 * np.max(np.abs(r["z"])) / np.sqrt(np.mean(r["z"] ** 2))
+
+
+@pytest.mark.parametrize("blk", [12, 16])
+def test_c4_full_size_sampled_blocks(env, blk):
+    """d = 2^27, M = 8, layered dynamic range: the whole round on the GPU, oracle on sampled blocks."""
+    O, B, inputs, dev = env
+    d, M = 1 << 27, 8
+    gs = inputs.workload("c4")
+    nb = d >> blk
+    nj = max(1, (1 << 17) >> blk)                      # 2^17 coordinates per sampled range
+    ranges = [(0, nj), (nb // 2 + 3, nj), (nb - nj, nj)]
+    rep = check_sampled_blocks(O, B, gs, d=d, M=M, block_log2=blk, seed=0xF05D + 4, rnd=0, device=dev, block_ranges=ranges)
+    print(rep, flush=True)
+    assert rep["uplink_mismatch"] == 0 and rep["downlink_mismatch"] == 0, rep
+    assert rep["lam_rel_err"] <= 1e-6 and rep["lam_s_rel_err"] <= 1e-6, rep
+    assert rep["decode_rel_l2"] <= 1e-5, rep
