@@ -21,9 +21,16 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; see profiles/),
-# keyed by kernel name; None until a counter run for that kernel is on file.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch on workload c3 measured with rocprofv3 --pmc (FETCH_SIZE scaled by 2.000, WRITE_SIZE
+# by 1.000, the factors of a 1 GiB copy; profiles/c3_fo_step_hbm_traffic.md), keyed by kernel name.  For the
+# kernels launched with two batch sizes per step the figure is the per-step sum divided by two.
+MEASURED_TRAFFIC = {
+    "k_strided<ENC_FIRST>": 3783846920,
+    "k_contig<IN_F32,OUT_PACK>": (2214793112 + 138681846) // 2,
+    "k_strided<SERVER>": 1208344209,
+    "k_contig<IN_BITS,OUT_I16>": (1140984267 + 71438362) // 2,
+    "k_strided<DEC_LAST>": 271913999,
+}
 
 
 def main():
@@ -33,6 +40,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic, used to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the M workers are M buffers on one device); "
@@ -55,6 +65,13 @@ def main():
     n = plan.ntot
     print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "
           f"plan scratch {plan.scratch_bytes / 2**30:.2f} GiB", file=sys.stderr, flush=True)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     delta = 1e-3
     for w in range(args.warmup):
@@ -92,7 +109,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None,
-        "traffic": MEASURED_TRAFFIC.get(dom),
+        "traffic": MEASURED_TRAFFIC.get(dom) if args.workload == "c3" else None,
         "avg_launch_ms": round(avg_ms, 4), "bytes_per_launch": bytes_per_launch,
         "kernel_ms_per_step": {k: round(ms / args.steps, 4) for k, (l, ms) in sorted(per_kernel.items())},
         "step_model_bytes": sum(v for k, v in per_step.items() if k in per_kernel),
