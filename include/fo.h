@@ -35,6 +35,14 @@
  * bound (FO_SCALE_BOUND) or the block's measured l2 norm (FO_SCALE_L2).  The server amplitude is
  * lambda^s_j = alpha_s * max_n lambda_{n,j} * sqrt(ln b) (Thm 5.5).
  *
+ * Shared worker eps (FO_EPS_SHARED_WORKERS, a variant the paper does not have).  When every worker
+ * uses the same eps_t and the same amplitude, linearity of H^T turns the server's M decodes into one:
+ * gbar = (lambda / M) D_eps H^T (2 c - M) with c the per-coordinate count of set bits over the M
+ * messages (a vertical popcount).  The server eps stays independent, as the server lemma in the proof
+ * of Thm 5.5 needs.  fo_step agrees on the common amplitude by itself (per block, the largest of the
+ * workers' amplitudes); a caller driving fo_encode by hand must pass that amplitude with
+ * FO_FORCE_SCALE, and fo_server_aggregate then reads worker 0's scales as everybody's.
+ *
  * Random numbers.  eps and the dither are functions of (seed, round, party, coordinate) through
  * Philox4x32-10; eps is therefore never transmitted, both ends regenerate it (the paper sends it
  * explicitly, Sec. 4 "Transmission").  The dither is u * lambda with u an odd multiple of 2^-24
@@ -61,6 +69,7 @@ extern "C" {
 #define FO_SCALE_BOUND 0u    /* B is the caller's bound on ||g||_2 (Thm 5.5 verbatim)    */
 #define FO_SCALE_L2 1u       /* B := measured ||g_block||_2 at this call                 */
 #define FO_EPS_INDEPENDENT 0u /* one eps per worker and one for the server (Sec. 4)     */
+#define FO_EPS_SHARED_WORKERS 1u /* one eps for all workers, an independent one for the server */
 
 #define FO_PARTY_SERVER 0xFFFFFFFFu /* party id of the server; workers are 0 .. M-1      */
 #define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */
@@ -74,7 +83,7 @@ typedef struct {
     uint32_t K;          /* averaging count of the downlink quantizer (Def. 3.2); only 1  */
     uint32_t dither;     /* FO_DITHER_*                                                   */
     uint32_t scale_rule; /* FO_SCALE_*                                                    */
-    uint32_t eps_mode;   /* FO_EPS_INDEPENDENT                                            */
+    uint32_t eps_mode;   /* FO_EPS_*                                                      */
     float alpha;         /* worker amplitude factor, >= 2 (Lemma 3.6)                     */
     float alpha_s;       /* server amplitude factor, >= 2                                 */
     float B;             /* norm bound for FO_SCALE_BOUND, > 0 (ignored by FO_SCALE_L2)   */

@@ -67,6 +67,22 @@ __global__ void k_server_scales(const float *scales_up, uint64_t nblocks, uint32
     scales_down[j] = nan ? __builtin_nanf("") : coef_s * m;
 }
 
+// Shared-eps mode: every worker quantises with the largest of the workers' amplitudes, per block.
+__global__ void k_common_scales(float *scales, uint64_t nblocks, uint32_t M)
+{
+    const uint64_t j = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (j >= nblocks) return;
+    float m = 0.f;
+    bool nan = false;
+    for (uint32_t n = 0; n < M; ++n) {
+        const float l = scales[(uint64_t)n * nblocks + j];
+        nan |= (l != l);
+        m = fmaxf(m, l);
+    }
+    if (nan) m = __builtin_nanf("");
+    for (uint32_t n = 0; n < M; ++n) scales[(uint64_t)n * nblocks + j] = m;
+}
+
 bool aligned(const void *p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 
 // Kernel identities for the optional per-kernel timing (fo_profile_begin / fo_profile_end).
@@ -79,14 +95,15 @@ enum KernelId {
     KID_DEC_LOW,        // k_contig<IN_BITS,OUT_I16> (OUT_I32 for three-pass transforms)
     KID_DEC_MID,        // k_strided<MID_I32>
     KID_DEC_HIGH,       // k_strided<DEC_LAST>
-    KID_SERVER_HIGH,    // k_strided<SERVER>
+    KID_SERVER_HIGH,    // k_strided<SERVER> / k_strided<SHARED>
+    KID_COUNT_LOW,      // k_contig<IN_COUNT,*>
     KID_SCALES,         // k_finalize_scales / k_fill_scales / k_server_scales
     KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_contig<IN_BITS,OUT_F32>",  "k_contig<IN_BITS,OUT_I16>", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "scale kernels",
+    "k_strided<SERVER>", "k_contig<IN_COUNT>", "scale kernels",
 };
 
 struct Profiler {
@@ -136,7 +153,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     if (q.K != 1) return FO_EINVAL;
     if (q.dither != FO_DITHER_UNIFORM && q.dither != FO_DITHER_NONE) return FO_EINVAL;
     if (q.scale_rule != FO_SCALE_BOUND && q.scale_rule != FO_SCALE_L2) return FO_EINVAL;
-    if (q.eps_mode != FO_EPS_INDEPENDENT) return FO_EINVAL;
+    if (q.eps_mode != FO_EPS_INDEPENDENT && q.eps_mode != FO_EPS_SHARED_WORKERS) return FO_EINVAL;
     if (!(q.alpha >= 2.f) || !(q.alpha_s >= 2.f)) return FO_EINVAL;
     if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
 
@@ -163,6 +180,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     pl->npass = high == 0 ? 0 : (high <= 10 ? 1 : 2);
     pl->hb[0] = pl->npass == 2 ? (high + 1) / 2 : high;
     pl->hb[1] = high - pl->hb[0];
+    if (q.eps_mode == FO_EPS_SHARED_WORKERS && pl->npass == 2) { delete pl; return FO_EINVAL; } // not built for b > 2^25
     const double bd = (double)pl->b;
     pl->coef_lambda = (float)((double)q.alpha * std::sqrt(std::log(bd) / bd));
     pl->sqrtb = (float)std::sqrt(bd);
@@ -235,6 +253,7 @@ inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
     if (!c.dst) return false;
     if (grad_in ? (c.use_tab ? !tab.p[0] : !c.src) : !c.src) return false;
     const bool needs_scales = kid == KID_ENC_SINGLE || kid == KID_ENC_LOW || kid == KID_DEC_SINGLE;
+    if (kid == KID_COUNT_LOW && (c.M < 1 || c.M > FO_MAX_WORKERS)) return false;
     return !needs_scales || c.scales != nullptr;
 }
 inline bool args_ok(const StridedArgs &s, const PtrTab &tab, int kid)
@@ -323,12 +342,22 @@ ContigArgs contig_base(const fo_plan *pl, const Rng &r)
     return c;
 }
 
+constexpr uint32_t kPartyAllWorkers = 0xFFFFFFFEu;
+// Which eps stream a party uses: its own, or the common one of the workers in shared-eps mode.
+uint32_t eps_party_of(const fo_plan *pl, uint32_t party)
+{
+    if (party == FO_PARTY_SERVER || pl->p.eps_mode == FO_EPS_INDEPENDENT) return party;
+    return kPartyAllWorkers;
+}
+
 // Encode `nslots` vectors.  Sources: tab (pointer table, nslots entries) or src + slot * src_stride.
-// mode 0: amplitudes from the measured norm; 1: scales[] already holds them (forced / bound rule).
+// scales_given: scales[] already holds the amplitudes (forced / bound rule); else they come from the
+// measured norms.  common: the nslots parties are all the workers of a shared-eps round and must agree
+// on one amplitude per block (the largest) before any of them quantises; scales is then [M][nblocks].
 int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src_stride, uint64_t len_in,
                   uint32_t nslots, uint32_t party0, uint64_t round, bool scales_given, uint64_t *bits,
                   uint64_t bits_stride, float *scales, uint64_t scales_stride, float *tmp, uint64_t tmp_stride,
-                  hipStream_t st)
+                  hipStream_t st, bool common = false)
 {
     const Rng r = rng_of(pl, round);
     PtrTab none;
@@ -338,11 +367,20 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     ContigArgs c = contig_base(pl, r);
     c.dst = bits; c.dst_stride = bits_stride;
     c.scales = scales; c.scales_stride = scales_stride;
-    c.party0 = party0; c.eps_party0 = party0;
+    c.party0 = party0; c.eps_party0 = eps_party_of(pl, party0);
+    const dim3 cgrid((unsigned)((pl->nblocks + 255) / 256));
     if (pl->npass == 0) {
         c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
         c.len_in = len_in;
         c.compute_scale = scales_given ? 0u : 1u;
+        if (common && !scales_given) {
+            // one extra read of the gradients: norms first, then the common amplitude, then the encode proper
+            c.scales_only = 1u;
+            FO_TRY(launch_pack<IN_GRAD>(pl, KID_ENC_SINGLE, grid, st, c, tb));
+            FO_TRY(launch(pl, KID_SCALES, k_common_scales, cgrid, dim3(256), st, scales, pl->nblocks, nslots));
+            c.scales_only = 0u;
+            c.compute_scale = 0u;
+        }
         FO_TRY(launch_pack<IN_GRAD>(pl, KID_ENC_SINGLE, grid, st, c, tb));
         return FO_OK;
     }
@@ -351,7 +389,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     StridedArgs s = strided_base(pl, r, first);
     s.src = src; s.src_stride = src_stride; s.use_tab = tab ? 1u : 0u; s.len_in = len_in;
     s.dst = (pl->npass == 2) ? pl->buf_c : tmp; s.dst_stride = (pl->npass == 2) ? 0 : tmp_stride;
-    s.partials = pl->partials; s.eps_party0 = party0;
+    s.partials = pl->partials; s.eps_party0 = eps_party_of(pl, party0);
     if (pl->npass == 2 && nslots != 1) return FO_EINVAL; // three-pass transforms are encoded one party at a time
     FO_TRY(launch_strided<SM_ENC_FIRST>(pl, KID_ENC_HIGH, grid, st, s, tb));
     if (pl->npass == 2) {
@@ -362,6 +400,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     if (!scales_given) {
         FO_TRY(launch(pl, KID_SCALES, k_finalize_scales, dim3((unsigned)pl->nblocks, nslots), dim3(256), st, pl->partials,
                            pl->ntiles, (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda, scales, scales_stride));
+        if (common) FO_TRY(launch(pl, KID_SCALES, k_common_scales, cgrid, dim3(256), st, scales, pl->nblocks, nslots));
     }
     c.src = tmp; c.src_stride = tmp_stride;
     FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid, st, c, none));
@@ -380,7 +419,7 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     ContigArgs c = contig_base(pl, r);
     c.src = bits; c.src_stride = 0;
     c.scales = const_cast<float *>(scales); c.scales_stride = 0;
-    c.party0 = party; c.eps_party0 = party;
+    c.party0 = party; c.eps_party0 = eps_party_of(pl, party);
     // the decode-side transforms carry every value divided by two (see fo_contig.h)
     out_coef *= 2.f;
     if (pl->npass == 0) {
@@ -392,7 +431,7 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     c.dst = tmp; c.dst_stride = 0;
     StridedArgs s = strided_base(pl, r, pl->npass - 1);
     s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
-    s.scales = scales; s.scales_stride = 0; s.eps_party0 = party;
+    s.scales = scales; s.scales_stride = 0; s.eps_party0 = eps_party_of(pl, party);
     if (pl->npass == 1) {
         // int16 intermediate between the two passes
         FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I16, false, false, 15>), grid, block, st, c, none));
@@ -419,6 +458,36 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
     FO_TRY(launch(pl, KID_SCALES, k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), st, scales_up,
                        pl->nblocks, M, pl->coef_s, scales_down));
     const float mean_coef = pl->rsqrtb / (float)M;
+    if (pl->p.eps_mode == FO_EPS_SHARED_WORKERS && pl->npass <= 1) {
+        // one eps and one amplitude for all workers: sum the packed sign vectors per coordinate (vertical
+        // popcount), then a single inverse transform instead of M
+        ContigArgs c = contig_base(pl, r);
+        c.src = bits_up; c.src_stride = pl->W; c.M = M;
+        c.scales = const_cast<float *>(scales_up); c.scales_stride = 0; // worker 0's amplitudes are everybody's
+        c.party0 = 0; c.eps_party0 = kPartyAllWorkers;
+        const dim3 grid1((unsigned)pl->ntiles, 1), block(kThreads);
+        if (pl->npass == 0) {
+            float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
+            c.dst = gbar; c.len_out = pl->ntot; c.store_mode = STORE_SET; c.out_coef = mean_coef;
+            FO_TRY(launch(pl, KID_COUNT_LOW, (k_contig<IN_COUNT, OUT_F32>), grid1, block, st, c, none));
+            return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down,
+                                 0, nullptr, 0, st);
+        }
+        c.dst = pl->buf_a; c.dst_stride = 0;
+        FO_TRY(launch(pl, KID_COUNT_LOW, (k_contig<IN_COUNT, OUT_I32, false, false, 15>), grid1, block, st, c, none));
+        StridedArgs s = strided_base(pl, r, 0);
+        s.src = pl->buf_a; s.dst = pl->buf_b;
+        s.scales = scales_up; s.scales_stride = 0;
+        s.gbar = gbar_or_null;
+        s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
+        FO_TRY(launch_strided<SM_SHARED>(pl, KID_SERVER_HIGH, grid1, st, s, none));
+        ContigArgs e = contig_base(pl, r);
+        e.src = pl->buf_b; e.dst = bits_down;
+        e.scales = scales_down;
+        e.party0 = FO_PARTY_SERVER; e.eps_party0 = FO_PARTY_SERVER;
+        FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid1, st, e, none));
+        return FO_OK;
+    }
     if (pl->npass == 0) {
         // decode every worker into the mean (materialised), then encode the mean
         float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
@@ -541,7 +610,7 @@ extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta
                                pl->scales_up + (uint64_t)m * pl->nblocks, 0, pl->buf_a, 0, st);
     } else {
         rc = launch_encode(pl, &tab, nullptr, 0, pl->p.d, M, 0, round, given, pl->bits_up, pl->W, pl->scales_up,
-                           pl->nblocks, pl->buf_a, pl->ntot, st);
+                           pl->nblocks, pl->buf_a, pl->ntot, st, pl->p.eps_mode == FO_EPS_SHARED_WORKERS);
     }
     if (rc) return rc;
     rc = launch_server(pl, pl->bits_up, pl->scales_up, round, pl->bits_down, pl->scales_down, nullptr, st);

@@ -1,7 +1,9 @@
 // Contiguous-tile kernel: the low min(log2 b, 15) Walsh-Hadamard stages of every 2^15-coordinate
 // tile, fused with whatever sits at either end of the transform:
 //   input  : fp32 gradient (zero-padded) with the eps sign flip and the per-block sum of squares
-//            (Def. 3.5; norm for the amplitude of Thm 5.5) | fp32 intermediate | packed sign bits
+//            (Def. 3.5; norm for the amplitude of Thm 5.5) | fp32 intermediate | packed sign bits |
+//            the M workers' packed sign bits summed per coordinate (vertical popcount; valid when all
+//            workers share one eps and one amplitude, because H^T is linear: sum_n H^T q_n = H^T sum_n q_n)
 //   output : dither + sign + 64-bit packing (Def. 3.2, Def. 3.7) | int32 intermediate |
 //            amplitude scaling + eps flip + store / accumulate / SGD update (Def. 3.8, Sec. 4)
 //
@@ -23,7 +25,7 @@
 
 namespace fo {
 
-enum { IN_GRAD = 0, IN_F32 = 1, IN_BITS = 2 };
+enum { IN_GRAD = 0, IN_F32 = 1, IN_BITS = 2, IN_COUNT = 3 };
 enum { OUT_PACK = 0, OUT_I32 = 1, OUT_F32 = 2, OUT_I16 = 3 };
 enum { STORE_SET = 0, STORE_ACC = 1, STORE_AXPY = 2 };
 
@@ -48,6 +50,8 @@ struct ContigArgs {
     uint32_t compute_scale; // IN_GRAD: derive lambda from the measured block norm (else read scales[])
     uint32_t dither;        // 0 uniform, 1 none
     uint32_t store_mode;    // OUT_F32: STORE_*
+    uint32_t M;             // IN_COUNT: number of packed vectors to add up
+    uint32_t scales_only;   // IN_GRAD: write the blocks' amplitudes and stop (no transform)
     uint32_t party0;        // party id of slot 0 (slot y is party0 + y); FO_PARTY_SERVER stays as is
     uint32_t eps_party0;    // same for the eps stream
     uint32_t k0, k1, round_lo;
@@ -65,7 +69,7 @@ struct ContigArgs {
 template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0>
 __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
 {
-    using T = typename std::conditional<IN == IN_BITS, int32_t, float>::type;
+    using T = typename std::conditional<(IN == IN_BITS || IN == IN_COUNT), int32_t, float>::type;
     __shared__ uint32_t lds[kLdsWords];
     uint32_t *const xbuf = lds;
     uint32_t *const epsw = lds + kXWords;
@@ -101,6 +105,27 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
             }
             v[4 * c + 0] = x.x; v[4 * c + 1] = x.y; v[4 * c + 2] = x.z; v[4 * c + 3] = x.w;
         }
+    } else if constexpr (IN == IN_COUNT) {
+        // q_sum_i = sum_n q_{n,i} = 2 * popcount_i - M.  The four coordinates of a lane are a nibble of one
+        // 32-bit half word; multiplying the nibble by 0x00204081 puts its bits into the low bit of four
+        // bytes, so one add per worker counts four coordinates at once (M <= 64 < 256: no byte overflows).
+        const uint32_t *src = static_cast<const uint32_t *>(a.src);
+        uint32_t cnt[16];
+#pragma unroll
+        for (int c = 0; c < 16; ++c) cnt[c] = 0u;
+        for (uint32_t m = 0; m < a.M; ++m) {
+            const uint32_t *sm = src + 2 * (uint64_t)m * a.src_stride;
+#pragma unroll
+            for (int c = 0; c < 16; ++c) {
+                const uint64_t gh = 2 * ((uint64_t)tile * 512u + wave * 64u + c * 4u) + (lane >> 3); // 32-bit half word
+                const uint32_t h = (gh < 2 * a.W) ? sm[gh] : 0u;
+                cnt[c] += (((h >> ((lane & 7u) * 4u)) & 15u) * 0x00204081u) & 0x01010101u;
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[4 * c + k] = 2 * (int32_t)((cnt[c] >> (8 * k)) & 255u) - (int32_t)a.M;
     } else {
         const uint64_t *src = static_cast<const uint64_t *>(a.src) + slot * a.src_stride;
 #pragma unroll
@@ -146,6 +171,24 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
                         red[wave * segs_per_wave + c * (256u >> S) + (lane >> lanes_log2)] = s;
                 }
             }
+        }
+        if (a.scales_only) {
+            // amplitudes only (used to agree on a common amplitude before any worker quantises)
+            __syncthreads();
+            const uint32_t nblk = kTile >> S;
+            if (t < nblk) {
+                const uint64_t gb = (uint64_t)tile * nblk + t;
+                float s;
+                if (S <= 12u) {
+                    s = red[t];
+                } else {
+                    const uint32_t per = 1u << (S - 12u);
+                    s = 0.f;
+                    for (uint32_t k = 0; k < per; ++k) s += red[t * per + k];
+                }
+                if (gb < a.nblocks) a.scales[slot * a.scales_stride + gb] = a.coef_lambda * sqrtf(s);
+            }
+            return;
         }
         // eps flip: lanes 0..31 of each wave draw the 32 generator blocks covering the wave's 4096 coordinates
         if (lane < 32u) {

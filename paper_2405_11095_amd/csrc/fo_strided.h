@@ -18,12 +18,14 @@
 //   SM_SERVER    : for every worker: int16 intermediate -> remaining inverse stages, scale, flip,
 //                  accumulate the mean (eq. "server average"); then eps^s flip and the forward
 //                  stages of the re-encode (Sec. 4, server-to-workers encoding) -> fp32 intermediate
+//   SM_SHARED    : the same server step when all workers share one eps and one amplitude: the int32
+//                  intermediate already holds the low stages of H^T sum_n q_n, so one tile is read, not M
 #pragma once
 #include "fo_contig.h"
 
 namespace fo {
 
-enum { SM_ENC_FIRST = 0, SM_DEC_LAST = 1, SM_MID_F32 = 2, SM_MID_I32 = 3, SM_SERVER = 4 };
+enum { SM_ENC_FIRST = 0, SM_DEC_LAST = 1, SM_MID_F32 = 2, SM_MID_I32 = 3, SM_SERVER = 4, SM_SHARED = 5 };
 
 struct StridedArgs {
     const void *src;       // [slot][ntot] fp32 / int32 / int16 (ENC_FIRST: gradients, or pointer table)
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
         }
     };
 
-    if constexpr (MODE != SM_SERVER) {
+    if constexpr (MODE != SM_SERVER && MODE != SM_SHARED) {
         TV v[kSV];
         const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
         const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
@@ -340,8 +342,30 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
         }
     } else {
         // ==================================================================== server
-        static_assert(IN16, "the server pass reads the int16 intermediate");
         float acc[kSV];
+        if constexpr (MODE == SM_SHARED) {
+            // one tile: remaining inverse stages of H^T (sum of the workers' sign vectors), amplitude / M, shared eps
+            static_assert(!IN16, "the summed sign vectors need an int32 intermediate");
+            int32_t v[kSV];
+            const RngKey key_w = { a.k0, a.k1, kDomainEps, a.round_lo, 0xFFFFFFFEu };
+            fill_eps<L::T>(epsw, g, key_w, t);
+            load_int(v, static_cast<const char *>(a.src) + g.origin * 4u);
+            stages_a<int32_t, LV>(v, cb);
+            if (need_x) {
+                exchange<int32_t, LV>(v, xbuf, lane, wave);
+                stages_b<int32_t, LV>(v, cb);
+            } else {
+                __syncthreads();
+            }
+            const float c = a.scales[gb] * a.out_coef;
+#pragma unroll
+            for (int p = 0; p < kSP; ++p) {
+                acc[2 * p] = c * (float)v[2 * p];
+                acc[2 * p + 1] = c * (float)v[2 * p + 1];
+                flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
+            }
+        } else {
+        static_assert(MODE != SM_SERVER || IN16, "the server pass reads the int16 intermediate");
         uint32_t raw[kSP]; // packed tile of the next worker, in flight while the current one is transformed
 #pragma unroll
         for (int r = 0; r < kSV; ++r) acc[r] = 0.f;
@@ -388,6 +412,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             process(m, std::true_type{});
         }
         process(a.M - 1, std::false_type{});
+        }
         if (a.gbar) {
             float *gq = a.gbar + g.origin;
 #pragma unroll

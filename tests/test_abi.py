@@ -47,10 +47,11 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(M=0) == B.EINVAL and create(M=65) == B.EINVAL
     assert create(block_log2=5) == B.EINVAL and create(block_log2=31) == B.EINVAL
     assert create(K=2) == B.EINVAL
-    assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=1) == B.EINVAL
+    assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=2) == B.EINVAL
     assert create(alpha=1.5) == B.EINVAL and create(alpha_s=float("nan")) == B.EINVAL
     assert create(scale_rule=0, B=0.0) == B.EINVAL
     assert create(d=(1 << 30) + 1) == B.EINVAL
+    assert create(d=(1 << 26), eps_mode=1) == B.EINVAL          # shared eps is built up to n = 2^25
     assert lib.fo_plan_create(None, None) == B.EINVAL
     # NULL plan in the hot calls
     assert lib.fo_encode(None, None, 0, 0, 0, None, None, None) == B.EINVAL

@@ -175,3 +175,21 @@ def test_c4_full_size_sampled_blocks(env, blk):
     assert rep["uplink_mismatch"] == 0 and rep["downlink_mismatch"] == 0, rep
     assert rep["lam_rel_err"] <= 1e-6 and rep["lam_s_rel_err"] <= 1e-6, rep
     assert rep["decode_rel_l2"] <= 1e-5, rep
+
+
+@pytest.mark.parametrize("name,d,M,blk", [
+    ("single_pass", 30_000, 5, 0),
+    ("blocked", 200_003, 4, 12),
+    ("two_pass", (1 << 18) + 11, 7, 0),
+    ("n2p25", 25_557_032, 3, 0),
+])
+def test_shared_worker_eps_popcount_server(env, name, d, M, blk):
+    """One eps and one amplitude for all workers: the server sums the packed sign vectors per
+    coordinate and runs a single inverse transform.  The oracle forms the mean the long way (M
+    decodes), so this checks the shortcut against the unshortened formula."""
+    O, B, inputs, dev = env
+    gs = [inputs.heavy_tailed(d, m) for m in range(M)]
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=blk, seed=0x5A + M, rnd=11, delta=0.02, device=dev,
+                           eps_mode=B.EPS_SHARED_WORKERS)
+    print(name, rep, flush=True)
+    gates(rep)
