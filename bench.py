@@ -39,6 +39,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--eps-mode", default="independent", choices=["independent", "shared"],
+                    help="independent: the paper's protocol (default, the headline number); shared: one eps for all "
+                         "workers and the popcount server")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic, used to scale "
@@ -61,7 +64,8 @@ def main():
     gs_host = inputs.workload(args.workload)
     gs = [torch.from_numpy(g).to(dev) for g in gs_host]
     x = torch.zeros(d, dtype=torch.float32, device=dev)
-    plan = B.Plan(d=d, M=M, block_log2=0, seed=0xF05D + 3)
+    eps_mode = B.EPS_SHARED_WORKERS if args.eps_mode == "shared" else B.EPS_INDEPENDENT
+    plan = B.Plan(d=d, M=M, block_log2=0, seed=0xF05D + 3, eps_mode=eps_mode)
     n = plan.ntot
     print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "
           f"plan scratch {plan.scratch_bytes / 2**30:.2f} GiB", file=sys.stderr, flush=True)
@@ -97,8 +101,9 @@ def main():
     per_step = {
         "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
         "k_contig<IN_F32,OUT_PACK>": (M + 1) * (4 * n + W8),
-        "k_contig<IN_BITS,OUT_I16>": (M + 1) * (W8 + 4 * n),
-        "k_strided<SERVER>": M * 4 * n + 4 * n,
+        "k_contig<IN_BITS,OUT_I16>": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
+        "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
+        "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
         "k_contig<IN_BITS,OUT_F32>": M * (W8 + 8 * n) + (W8 + 8 * d),
@@ -109,7 +114,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None,
-        "traffic": MEASURED_TRAFFIC.get(dom) if args.workload == "c3" else None,
+        "traffic": MEASURED_TRAFFIC.get(dom) if (args.workload == "c3" and args.eps_mode == "independent") else None,
         "avg_launch_ms": round(avg_ms, 4), "bytes_per_launch": bytes_per_launch,
         "kernel_ms_per_step": {k: round(ms / args.steps, 4) for k, (l, ms) in sorted(per_kernel.items())},
         "step_model_bytes": sum(v for k, v in per_step.items() if k in per_kernel),
@@ -121,7 +126,7 @@ def main():
         from oracle import fo_oracle as O
         Ms = min(8, M)                                   # bounded sample: the first Ms workers, full d
         nthreads = max(1, min(Ms, 16, os.cpu_count() or 1))
-        p = O.params(d=d, M=Ms, block_log2=0, seed=0xF05D + 3)
+        p = O.params(d=d, M=Ms, block_log2=0, seed=0xF05D + 3, eps_mode=1 if args.eps_mode == "shared" else 0)
         xo = np.zeros(d, dtype=np.float64)
         c0 = time.perf_counter()
         O.round_trip(p, gs_host[:Ms], xo, delta, 0, nthreads=nthreads)
@@ -137,7 +142,7 @@ def main():
         "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: d={d} fp32 padded to n={n}, M={M} workers, full-length randomized FWHT, "
-                               f"uniform dither, L2 scale rule, alpha=alpha_s=2, independent eps, one fo_step per step",
+                               f"uniform dither, L2 scale rule, alpha=alpha_s=2, {args.eps_mode} eps, one fo_step per step",
                    "d": d, "n": n, "M": M, "block_log2": 0},
         "roofline": roofline, "cpu_baseline": cpu,
     }
