@@ -378,30 +378,31 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
         // with worker m + 1 as soon as they have been unpacked
         auto process = [&](uint32_t m, auto prefetch) {
             constexpr bool PREFETCH = decltype(prefetch)::value;
-            int32_t buf[kSV];
+            // fp32 butterflies: every value is an integer below 2^24 in magnitude, so each sum is exact
+            float buf[kSV];
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
-                buf[2 * p] = (int32_t)(int16_t)(raw[p] & 0xFFFFu);
-                buf[2 * p + 1] = (int32_t)raw[p] >> 16;
+                buf[2 * p] = (float)(int16_t)(raw[p] & 0xFFFFu);
+                buf[2 * p + 1] = (float)((int32_t)raw[p] >> 16);
             }
             if constexpr (PREFETCH) request(m + 1);
             const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
             __syncthreads(); // the previous worker's eps words and exchange buffer are no longer read
             fill_eps<L::T>(epsw, g, key_eps, t);
-            stages_a<int32_t, LV>(buf, cb);
+            stages_a<float, LV>(buf, cb);
             if (need_x) {
-                exchange<int32_t, LV>(buf, xbuf, lane, wave);
-                stages_b<int32_t, LV>(buf, cb);
+                exchange<float, LV>(buf, xbuf, lane, wave);
+                stages_b<float, LV>(buf, cb);
             } else {
                 __syncthreads();
             }
-            const float c = a.scales[(uint64_t)m * a.scales_stride + gb] * a.out_coef;
+            // acc += (+-c) * value: the eps sign goes into the (non-negative) coefficient's sign bit
+            const uint32_t cbits = __float_as_uint(a.scales[(uint64_t)m * a.scales_stride + gb] * a.out_coef);
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
-                float y0 = c * (float)buf[2 * p], y1 = c * (float)buf[2 * p + 1];
-                flip_pair(y0, y1, epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
-                acc[2 * p] += y0;
-                acc[2 * p + 1] += y1;
+                const uint32_t w = epsw[(ut_out >> 5) + (upair_out(p) >> 5)];
+                acc[2 * p] = fmaf(buf[2 * p], __uint_as_float(((w >> eshift) << 31) | cbits), acc[2 * p]);
+                acc[2 * p + 1] = fmaf(buf[2 * p + 1], __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits), acc[2 * p + 1]);
             }
         };
         request(0);
