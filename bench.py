@@ -28,7 +28,7 @@ MEASURED_TRAFFIC = {
     "k_strided<ENC_FIRST>": 3783846920,
     "k_contig<IN_F32,OUT_PACK>": (2214793112 + 138681846) // 2,
     "k_strided<SERVER>": 1208344209,
-    "k_contig<IN_BITS,OUT_I16>": (1140984267 + 71438362) // 2,
+    "k_declow": (1140984267 + 71438362) // 2,
     "k_strided<DEC_LAST>": 271913999,
 }
 
@@ -101,7 +101,7 @@ def main():
     per_step = {
         "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
         "k_contig<IN_F32,OUT_PACK>": (M + 1) * (4 * n + W8),
-        "k_contig<IN_BITS,OUT_I16>": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
+        "k_declow": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,

@@ -10,6 +10,7 @@
 
 #include "../../include/fo.h"
 #include "fo_strided.h"
+#include "fo_declow.h"
 
 using namespace fo;
 
@@ -92,7 +93,7 @@ enum KernelId {
     KID_ENC_MID,        // k_strided<MID_F32>
     KID_ENC_LOW,        // k_contig<IN_F32,OUT_PACK>
     KID_DEC_SINGLE,     // k_contig<IN_BITS,OUT_F32>
-    KID_DEC_LOW,        // k_contig<IN_BITS,OUT_I16> (OUT_I32 for three-pass transforms)
+    KID_DEC_LOW,        // k_declow (k_contig<IN_BITS,OUT_I32> for three-pass transforms)
     KID_DEC_MID,        // k_strided<MID_I32>
     KID_DEC_HIGH,       // k_strided<DEC_LAST>
     KID_SERVER_HIGH,    // k_strided<SERVER> / k_strided<SHARED>
@@ -102,7 +103,7 @@ enum KernelId {
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
-    "k_contig<IN_BITS,OUT_F32>",  "k_contig<IN_BITS,OUT_I16>", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
+    "k_contig<IN_BITS,OUT_F32>",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
     "k_strided<SERVER>", "k_contig<IN_COUNT>", "scale kernels",
 };
 
@@ -256,6 +257,7 @@ inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
     if (kid == KID_COUNT_LOW && (c.M < 1 || c.M > FO_MAX_WORKERS)) return false;
     return !needs_scales || c.scales != nullptr;
 }
+inline bool args_ok(const ContigArgs &c, int) { return c.src && c.dst; } // k_declow
 inline bool args_ok(const StridedArgs &s, const PtrTab &tab, int kid)
 {
     if (!s.dst) return false;
@@ -434,7 +436,7 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     s.scales = scales; s.scales_stride = 0; s.eps_party0 = eps_party_of(pl, party);
     if (pl->npass == 1) {
         // int16 intermediate between the two passes
-        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I16, false, false, 15>), grid, block, st, c, none));
+        FO_TRY(launch(pl, KID_DEC_LOW, k_declow, grid, block, st, c));
         s.src = tmp;
         FO_TRY((launch_strided<SM_DEC_LAST, true>(pl, KID_DEC_HIGH, grid, st, s, none)));
         return FO_OK;
@@ -516,7 +518,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         ContigArgs c = contig_base(pl, r);
         c.src = bits_up; c.src_stride = pl->W;
         c.dst = pl->buf_a; c.dst_stride = pl->ntot;
-        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I16, false, false, 15>), dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c, none));
+        FO_TRY(launch(pl, KID_DEC_LOW, k_declow, dim3((unsigned)pl->ntiles, M), dim3(kThreads), st, c));
     }
     {
         StridedArgs s = strided_base(pl, r, 0);

@@ -1,0 +1,112 @@
+// Decode-side low stages straight from the packed sign bits: the fifteen Walsh-Hadamard stages of
+// every 2^15-coordinate tile of H^T q (Def. 3.8), q in {-1,+1}^n given as bits, result as int16.
+//
+// The data are small integers, which buys two things over the generic tile kernel:
+//   * the five stages on b0..b4 act on the 32 signs of one packed 32-bit word, and output j of that
+//     32-point transform is sum_i W_j(i) (2 c_i - 1) = 2 popcount(word ^ mask_j) - 32, where mask_j has
+//     bit i set when popcount(i & j) is odd: one xor and one bit count per output instead of an unpack
+//     and five additions;
+//   * every later stage adds or subtracts whole registers, so two int16 values ride in one register
+//     (the pair b0 = 0, 1, which is also the pair the int16 intermediate stores in one dword) and one
+//     packed add serves two butterflies.
+// As everywhere on the decode side the values are carried divided by two: popcount - 16 instead of
+// 2 popcount - 32, so the result of all fifteen stages fits int16 exactly.  The -16 is not applied per
+// value: a constant offset of 16 on every input of the remaining ten stages ends up as 16 * 2^10 on the
+// coordinates whose bits b5..b14 are all zero and nowhere else, and is taken off there at the end
+// (int16 arithmetic wraps, so the detour through the offset cannot lose anything).
+//
+// Index-bit choreography (dword = pair of coordinates, bits b1..b14):
+//   LA: regs = (b1,b2,b3,b4,b11)   lanes = (b5..b10)            waves = (b12,b13,b14)   stages b0..b4, b11
+//   LB: regs = (b5..b9)            lanes = (b1,b2,b3,b4,b11,b10)                        stages b5..b9, b10 (lane swap)
+//   LC: regs = (b12,b13,b14,b7,b8) lanes = (b1..b6)             waves = (b9,b10,b11)    stages b12,b13,b14
+#pragma once
+#include "fo_contig.h"
+
+namespace fo {
+
+typedef short s16x2 __attribute__((ext_vector_type(2)));
+
+constexpr uint32_t walsh_mask32(int j)
+{
+    uint32_t m = 0;
+    for (int i = 0; i < 32; ++i)
+        if (__builtin_popcount((unsigned)(i & j)) & 1) m |= 1u << i;
+    return m;
+}
+
+// Uses src, src_stride (64-bit words between slots), dst, dst_stride (int16 elements between slots) and W
+// of the argument block; the transform length is at least 2^15, so every tile is complete.
+__global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
+{
+    __shared__ uint32_t xbuf[kXWords];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
+
+    s16x2 v[32];
+
+    // ------------------------------------------------------------------ stages b0..b4 (layout LA)
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        const uint64_t gh = (uint64_t)tile * 1024u + wave * 128u + x * 64u + lane; // 32-bit half word
+        const uint32_t w = (gh < 2 * a.W) ? src[gh] : 0u;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint32_t hi = (uint32_t)__builtin_popcount(w ^ walsh_mask32(2 * k + 1));
+            const uint32_t both = (uint32_t)__builtin_popcount(w ^ walsh_mask32(2 * k)) + (hi << 16);
+            v[x * 16 + k] = __builtin_bit_cast(s16x2, both);
+        }
+    }
+    bfly<s16x2, 4, 32>(v); // b11
+
+    // ------------------------------------------------------------------ exchange LA -> LB (inside each half wave)
+    {
+        uint32_t *const wb = xbuf + wave * 2112u + (lane >> 5) * 1056u;
+        const uint32_t col = lane & 31u;
+#pragma unroll
+        for (int r = 0; r < 32; ++r) wb[r * 33 + col] = __builtin_bit_cast(uint32_t, v[r]);
+        wave_sync();
+#pragma unroll
+        for (int r = 0; r < 32; ++r) v[r] = __builtin_bit_cast(s16x2, wb[col * 33 + r]);
+    }
+    bfly<s16x2, 0, 32>(v);
+    bfly<s16x2, 1, 32>(v);
+    bfly<s16x2, 2, 32>(v);
+    bfly<s16x2, 3, 32>(v);
+    bfly<s16x2, 4, 32>(v);
+    bfly_lane5<s16x2, 32>(v); // b10
+
+    // ------------------------------------------------------------------ exchange LB -> LC (whole workgroup)
+    // Address = dword index D plus 16 words of padding per 1024: the writers' lanes spread over
+    // (b1..b4) and b11 (D bit 10), the readers' over (b1..b6).
+    __syncthreads(); // every wave is done with its part of the first exchange
+    {
+        const uint32_t b11 = (lane >> 4) & 1u, b10 = lane >> 5;
+        const uint32_t wofs = (lane & 15u) + b10 * 512u + b11 * 1024u + wave * 2048u + 16u * (b11 + 2u * wave);
+#pragma unroll
+        for (int r = 0; r < 32; ++r) xbuf[wofs + r * 16] = __builtin_bit_cast(uint32_t, v[r]);
+    }
+    __syncthreads();
+    {
+        const uint32_t rofs = lane + wave * 256u + 16u * (wave >> 2);
+#pragma unroll
+        for (int r = 0; r < 32; ++r) // register r = (b12,b13,b14,b7,b8)
+            v[r] = __builtin_bit_cast(s16x2, xbuf[rofs + ((r >> 3) & 1) * 64 + (r >> 4) * 128 + (r & 7) * (2048 + 32)]);
+    }
+    bfly<s16x2, 0, 32>(v);
+    bfly<s16x2, 1, 32>(v);
+    bfly<s16x2, 2, 32>(v);
+
+    // the popcount offset, gathered by the ten later stages on the coordinates with b5..b14 = 0
+    if (t < 16u) v[0] -= (s16x2)(16384, 16384);
+
+    // ------------------------------------------------------------------ store: a wave writes 256 contiguous bytes per register
+    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<int16_t *>(a.dst) + slot * a.dst_stride + ((uint64_t)tile << kTileLog2));
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        const uint32_t di = lane | ((uint32_t)((r >> 3) & 1) << 6) | ((uint32_t)(r >> 4) << 7) | (wave << 8) | ((uint32_t)(r & 7) << 11);
+        dst[di] = __builtin_bit_cast(uint32_t, v[r]);
+    }
+}
+
+} // namespace fo
