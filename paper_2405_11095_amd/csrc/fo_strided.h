@@ -178,6 +178,28 @@ __device__ __forceinline__ void exchange(T (&v)[1 << LV], uint32_t *xbuf, uint32
     }
 }
 
+// The same exchange in one pass, both members of a pair in one 8-byte access: needs room for the whole
+// tile (2^15 words), which a kernel that runs one workgroup per CU anyway can afford, and costs two
+// barriers less per call.
+template <typename T, int LV>
+__device__ __forceinline__ void exchange_wide(T (&v)[1 << LV], uint32_t *xbuf, uint32_t lane, uint32_t wave)
+{
+    constexpr int P = SL<LV>::P, NW = SL<LV>::NW;
+    uint2 *const wp = reinterpret_cast<uint2 *>(xbuf) + (lane | (wave << 6));
+    const uint2 *const rp = reinterpret_cast<const uint2 *>(xbuf) + (lane | (wave << (6 + NW)));
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+        wp[((p & ((1 << NW) - 1)) << (6 + NW)) | ((p >> NW) << (6 + 2 * NW))] =
+            make_uint2(__builtin_bit_cast(uint32_t, v[2 * p]), __builtin_bit_cast(uint32_t, v[2 * p + 1]));
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const uint2 d = rp[((p & ((1 << NW) - 1)) << 6) | ((p >> NW) << (6 + 2 * NW))];
+        v[2 * p] = __builtin_bit_cast(T, d.x);
+        v[2 * p + 1] = __builtin_bit_cast(T, d.y);
+    }
+}
+
 // flip a pair by bits 2k, 2k+1 of an eps word already shifted right by 2k
 __device__ __forceinline__ void flip_pair(float &x0, float &x1, uint32_t wshift)
 {
@@ -198,10 +220,13 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
     constexpr int kSV = L::V, kSP = L::P;
     constexpr bool FIN = (MODE == SM_ENC_FIRST || MODE == SM_MID_F32); // fp32 input
     using TV = typename std::conditional<FIN, float, int32_t>::type;
-    __shared__ uint32_t lds[kLdsWords];
+    // the server pass holds so many registers that one workgroup fills a CU: it takes the whole-tile exchange
+    constexpr bool WIDE = (MODE == SM_SERVER);
+    constexpr uint32_t kXW = WIDE ? kTile : kXWords;
+    __shared__ uint32_t lds[kXW + kEpsWords + kRedWords];
     uint32_t *const xbuf = lds;
-    uint32_t *const epsw = lds + kXWords;
-    float *const red = reinterpret_cast<float *>(lds + kXWords + kEpsWords + kLamWords);
+    uint32_t *const epsw = lds + kXW;
+    float *const red = reinterpret_cast<float *>(lds + kXW + kEpsWords);
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t slot = blockIdx.y;
@@ -391,7 +416,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             fill_eps<L::T>(epsw, g, key_eps, t);
             stages_a<float, LV>(buf, cb);
             if (need_x) {
-                exchange<float, LV>(buf, xbuf, lane, wave);
+                exchange_wide<float, LV>(buf, xbuf, lane, wave);
                 stages_b<float, LV>(buf, cb);
             } else {
                 __syncthreads();
@@ -430,7 +455,8 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
         if (need_x) {
             stages_b<float, LV>(acc, cb);
-            exchange<float, LV>(acc, xbuf, lane, wave);
+            if constexpr (WIDE) exchange_wide<float, LV>(acc, xbuf, lane, wave);
+            else exchange<float, LV>(acc, xbuf, lane, wave);
         }
         stages_a<float, LV>(acc, cb);
         float *dst = static_cast<float *>(a.dst) + g.origin;
