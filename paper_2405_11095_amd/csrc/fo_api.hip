@@ -298,7 +298,7 @@ int launch(fo_plan *pl, int kid, Kern kernel, dim3 grid, dim3 block, hipStream_t
 template <int MODE, bool IN16 = false>
 int launch_strided(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const StridedArgs &s, const PtrTab &tab)
 {
-    constexpr int LV = (MODE == SM_SERVER || MODE == SM_ENC_FIRST) ? 5 : 6;
+    constexpr int LV = (MODE == SM_SERVER || MODE == SM_SHARED || MODE == SM_ENC_FIRST) ? 5 : 6;
     if (s.hb == 10 && s.ls == (uint32_t)kTileLog2)
         return launch(pl, kid, k_strided<MODE, 10, IN16, LV>, grid, dim3(SL<LV>::T), st, s, tab);
     return launch(pl, kid, k_strided<MODE, 0, IN16, LV>, grid, dim3(SL<LV>::T), st, s, tab);

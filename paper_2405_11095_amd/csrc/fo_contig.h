@@ -319,8 +319,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
     if constexpr (OUT == OUT_PACK) {
         uint32_t my_lo = 0u, my_hi = 0u;
         const float tscale = a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m * 2^-24 with m odd
-#pragma unroll
-        for (int g = 0; g < 16; ++g) {
+        static_for<16>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
             uint32_t w[4] = { 0u, 0u, 0u, 0u };
             const uint32_t lg = local_of(2 * g); // b6 = b7 = 0
             float thr_g = 0.f;
@@ -328,6 +328,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
                 philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_dit, w);
                 if constexpr (!SMALLB) thr_g = lam[lg >> S] * tscale;
             }
+            uint64_t word[4];
 #pragma unroll
             for (int s = 0; s < 4; ++s) {
                 const int r = 2 * g + (s & 1) + 32 * (s >> 1); // slot s = b6 | b7 << 1
@@ -338,13 +339,17 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
                     const int32_t m = (int32_t)((w[s] >> 8) << 1) - 16777215; // 2 r + 1 - 2^24
                     tv = fmaf(thr, (float)m, tv);
                 }
-                const uint64_t word = __ballot(tv >= 0.f);
-                if (lane == (uint32_t)r) {
-                    my_lo = (uint32_t)word;
-                    my_hi = (uint32_t)(word >> 32);
-                }
+                word[s] = __ballot(tv >= 0.f);
             }
-        }
+            // the 64-bit word of register r goes to lane r: one write into that lane per half
+            settle_ballots(word[0], word[1], word[2], word[3]);
+            static_for<4>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                constexpr int r = 2 * g + (s & 1) + 32 * (s >> 1);
+                my_lo = write_lane<r>(my_lo, (uint32_t)word[s]);
+                my_hi = write_lane<r>(my_hi, (uint32_t)(word[s] >> 32));
+            });
+        });
         // lane j holds the word of register j
         const uint64_t gw = (uint64_t)tile * 512u +
                             ((lane & 1u) | ((lane >> 5) << 1) | (((lane >> 1) & 1u) << 2) | (wave << 3) | (((lane >> 2) & 7u) << 6));

@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace fo {
 
@@ -92,6 +93,34 @@ __device__ __forceinline__ float wave_sum(float s, int steps) // butterfly sum o
     for (int k = 0; k < 6; ++k)
         if (k < steps) s += __shfl_xor(s, 1 << k, 64);
     return s;
+}
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <int N, int I = 0, typename F>
+__device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<N, I + 1>(f);
+    }
+}
+
+// Returns v with lane LANE replaced by the wave-uniform value s (every other lane keeps its own).
+// v_writelane_b32 picks up a scalar register that a vector instruction (a compare) has just written
+// only after a few wait states: measured on gfx950, back-to-back use gives stale data now and then.
+// Callers put settle_ballots() between the compares and the lane writes.
+template <int LANE>
+__device__ __forceinline__ uint32_t write_lane(uint32_t v, uint32_t s)
+{
+    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(LANE));
+    return v;
+}
+
+// Orders four ballots before everything that follows and adds five wait states, whatever order the
+// compiler gave the compares; the idle cycles go to the other waves of the SIMD.
+__device__ __forceinline__ void settle_ballots(uint64_t w0, uint64_t w1, uint64_t w2, uint64_t w3)
+{
+    asm volatile("s_nop 4" ::"s"(w0), "s"(w1), "s"(w2), "s"(w3));
 }
 
 // One Walsh-Hadamard stage on lane bit 5 (partner = lane ^ 32).  v_permlane32_swap trades the

@@ -79,6 +79,20 @@ def test_determinism_and_seed_sensitivity(env):
         assert 0.3 < frac < 0.7
 
 
+def test_repeat_encodes_agree_large(env):
+    """Ten encodes of one 2^22-coordinate vector give the same 65536 words every time (the packed words
+    travel through scalar registers and lane writes, where a missed wait state shows up as rare stale words)."""
+    import torch
+    O, B, inputs, dev = env
+    d = 1 << 22
+    g = inputs.gaussian(d, 3)
+    plan = B.Plan(d=d, M=1, seed=11)
+    ref, lref = _encode(B, torch, dev, plan, g, 9, 0)
+    for _ in range(9):
+        b, l = _encode(B, torch, dev, plan, g, 9, 0)
+        assert torch.equal(b, ref) and torch.equal(l, lref)
+
+
 @pytest.mark.parametrize("name,kw", [
     ("bound_rule", dict(scale_rule=0, Bnorm=400.0)),
     ("no_dither", dict(dither=1)),
