@@ -336,8 +336,9 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
                 if constexpr (DITHER) {
                     float thr = thr_g;
                     if constexpr (SMALLB) thr = lam[local_of(r) >> S] * tscale;
-                    const int32_t m = (int32_t)((w[s] >> 8) << 1) - 16777215; // 2 r + 1 - 2^24
-                    tv = fmaf(thr, (float)m, tv);
+                    // m = 2 r + 1 - 2^24 for the 24-bit draw r; both conversions are exact
+                    const float m = fmaf((float)(w[s] >> 8), 2.f, -16777215.f);
+                    tv = fmaf(thr, m, tv);
                 }
                 word[s] = __ballot(tv >= 0.f);
             }

@@ -47,8 +47,9 @@ __device__ __forceinline__ void philox(uint32_t counter, const RngKey &key, uint
         // full 64-bit products: one v_mad_u64_u32 each instead of a low and a high multiply
         const uint64_t pa = (uint64_t)x0 * 0xD2511F53u;
         const uint64_t pb = (uint64_t)x2 * 0xCD9E8D57u;
-        x0 = (uint32_t)(pb >> 32) ^ x1 ^ ka;
-        x2 = (uint32_t)(pa >> 32) ^ x3 ^ kb;
+        // three-input xor (truth table 0x96) in one v_bitop3_b32
+        x0 = __builtin_amdgcn_bitop3_b32((uint32_t)(pb >> 32), x1, ka, 0x96);
+        x2 = __builtin_amdgcn_bitop3_b32((uint32_t)(pa >> 32), x3, kb, 0x96);
         x1 = (uint32_t)pb;
         x3 = (uint32_t)pa;
         ka += 0x9E3779B9u;
