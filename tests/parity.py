@@ -41,7 +41,7 @@ def compare_bits(gpu_bits, margin, lam, b):
 
 
 def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha=2.0, alpha_s=2.0,
-                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True, eps_mode=0):
+                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True, eps_mode=0, x0=None):
     """Runs encode x M, server, decode and fo_step on the GPU and compares every stage with the
     oracle.  Returns a report dict; asserts nothing (callers apply the gates)."""
     import torch
@@ -113,7 +113,8 @@ def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha
 
     # ---- fo_step: same messages as the calls made by hand, and the SGD update
     if check_step:
-        x0 = np.random.default_rng(12345).standard_normal(d).astype(np.float32)
+        if x0 is None:
+            x0 = np.random.default_rng(12345).standard_normal(d).astype(np.float32)
         x = torch.from_numpy(x0.copy()).to(device)
         plan.fo_step(gd, x, delta, rnd)
         torch.cuda.synchronize()
