@@ -43,6 +43,15 @@
  * workers' amplitudes); a caller driving fo_encode by hand must pass that amplitude with
  * FO_FORCE_SCALE, and fo_server_aggregate then reads worker 0's scales as everybody's.
  *
+ * Averaged downlink quantiser (K > 1).  The server's message is Q_{lambda^s,K} of Def. 3.2: the mean of K
+ * one-bit quantisers with independent dithers, which cuts the downlink's error term by K (Lemma "Second
+ * moment of the quantizer").  Coordinate i then carries the count c_i in {0..K} of dithers for which
+ * sign(z_i + tau_{k,i}) = +1, so (K / lambda^s) Q_{lambda^s,K}(z)_i = 2 c_i - K, stored as
+ * P = ceil(log2(K + 1)) bit planes of W words each (the paper's "log2(K+1) d bits"): plane p, word w,
+ * bit j  <->  bit p of c_{64 w + j}.  Every downlink buffer (bits_down; bits of party FO_PARTY_SERVER) is
+ * uint64[P][W]; fo_downlink_planes gives P.  Workers' messages always have K = 1 (Sec. 4).  K = 1 is the
+ * plain sign message, P = 1.  Limit: K <= FO_MAX_K and, for transforms longer than 2^15, K * b < 2^32.
+ *
  * Random numbers.  eps and the dither are functions of (seed, round, party, coordinate) through
  * Philox4x32-10; eps is therefore never transmitted, both ends regenerate it (the paper sends it
  * explicitly, Sec. 4 "Transmission").  The dither is u * lambda with u an odd multiple of 2^-24
@@ -75,12 +84,13 @@ extern "C" {
 #define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */
 
 #define FO_MAX_WORKERS 64u
+#define FO_MAX_K 255u
 
 typedef struct {
     uint64_t d;          /* logical gradient length, 1 <= d, padded length <= 2^30        */
     uint32_t M;          /* number of workers (the paper's N), 1 .. FO_MAX_WORKERS        */
     uint32_t block_log2; /* 0, or 6 .. 30                                                 */
-    uint32_t K;          /* averaging count of the downlink quantizer (Def. 3.2); only 1  */
+    uint32_t K;          /* averaging count of the downlink quantizer (Def. 3.2), 1 .. FO_MAX_K */
     uint32_t dither;     /* FO_DITHER_*                                                   */
     uint32_t scale_rule; /* FO_SCALE_*                                                    */
     uint32_t eps_mode;   /* FO_EPS_*                                                      */
@@ -102,11 +112,13 @@ size_t fo_padded_len(const fo_plan *plan);   /* ntot                            
 size_t fo_packed_words(const fo_plan *plan); /* W = ntot / 64                              */
 size_t fo_num_scales(const fo_plan *plan);   /* nblocks                                    */
 size_t fo_block_len(const fo_plan *plan);    /* b                                          */
+size_t fo_downlink_planes(const fo_plan *plan); /* P = ceil(log2(K + 1)) bit planes of a server message */
 size_t fo_scratch_bytes(const fo_plan *plan);
 /* Text of the last HIP error seen by this library on the calling thread (host string). */
 const char *fo_last_hip_error(void);
 
-/* Encoder E_{eps,lambda}(g) = sign(H D_eps g + tau), Def. 3.7 with K = 1 (Sec. 4, "Encoding").
+/* Encoder E_{eps,lambda}(g) = sign(H D_eps g + tau), Def. 3.7 (Sec. 4, "Encoding"); K = 1 for a worker,
+ * the plan's K for party FO_PARTY_SERVER (then bits is uint64[P][W], see "Averaged downlink quantiser").
  *   g       device fp32[len]: len = d for a worker, ntot when party == FO_PARTY_SERVER
  *   round   iteration t; party: worker id < M, or FO_PARTY_SERVER
  *   flags   0: scales[] is written with the amplitudes the rule gives;
@@ -115,8 +127,10 @@ const char *fo_last_hip_error(void);
 int fo_encode(fo_plan *plan, const float *g, uint64_t round, uint32_t party, uint32_t flags,
               uint64_t *bits, float *scales, void *hip_stream);
 
-/* Decoder D_{eps,lambda}(q) = lambda D_eps H^T q, Def. 3.8 with K = 1 (Sec. 4, "Decoding").
- *   bits device uint64[W], scales device fp32[nblocks] (as produced by the matching encode)
+/* Decoder D_{eps,lambda,K}(q) = (lambda / K) D_eps H^T q, Def. 3.8 (Sec. 4, "Decoding"); K = 1 for a worker's
+ * message, the plan's K for party FO_PARTY_SERVER.
+ *   bits device uint64[W] (uint64[P][W] for the server's message), scales device fp32[nblocks] (as produced
+ *   by the matching encode)
  *   out  device fp32[d]: the first d coordinates of the decoded vector                          */
 int fo_decode(fo_plan *plan, const uint64_t *bits, const float *scales, uint64_t round,
               uint32_t party, float *out, void *hip_stream);
@@ -124,7 +138,7 @@ int fo_decode(fo_plan *plan, const uint64_t *bits, const float *scales, uint64_t
 /* Server: gbar = (1/M) sum_n D_{eps_n,lambda_n}(q_n) (eq. "server average"), then the
  * (eps^s, lambda^s)-encoder applied to gbar in R^ntot (Sec. 4, "Server-to-workers").
  *   bits_up     device uint64[M][W];   scales_up   device fp32[M][nblocks]
- *   bits_down   device uint64[W] out;  scales_down device fp32[nblocks] out (lambda^s)
+ *   bits_down   device uint64[P][W] out (P = 1 when K = 1);  scales_down device fp32[nblocks] out (lambda^s)
  *   gbar_or_null  optional device fp32[ntot] out: the mean, materialised (for checking)         */
 int fo_server_aggregate(fo_plan *plan, const uint64_t *bits_up, const float *scales_up,
                         uint64_t round, uint64_t *bits_down, float *scales_down,
@@ -139,7 +153,7 @@ int fo_step(fo_plan *plan, const float *const *g, float *x, float delta, uint64_
             void *hip_stream);
 
 /* Device pointers into plan scratch holding the messages of the last fo_step on this plan:
- * bits_up [M][W], scales_up [M][nblocks], bits_down [W], scales_down [nblocks].  Any out
+ * bits_up [M][W], scales_up [M][nblocks], bits_down [P][W], scales_down [nblocks].  Any out
  * argument may be NULL.  Valid until the next hot call on the plan. */
 int fo_step_messages(fo_plan *plan, const uint64_t **bits_up, const float **scales_up,
                      const uint64_t **bits_down, const float **scales_down);

@@ -198,8 +198,9 @@ void orc_geometry(const orc_params *p, uint64_t *b, uint64_t *nblocks, uint64_t 
 /* ------------------------------------------------------------------------------------------ */
 
 /* q_i = sum_{k<K} sign(z_i + tau_{k,i}) in {-K, -K+2, ..., K}, i.e. (K/lambda) Q_{lambda,K}(z)_i,
- * for the n coordinates with global indices i0 .. i0+n-1.  margin (optional) receives
- * z_i + tau_{0,i}, the pre-quantisation value of the first dither. */
+ * for the n coordinates with global indices i0 .. i0+n-1.  margin (optional) receives the
+ * pre-quantisation value z_i + tau_{k,i} closest to zero over the K dithers (the one a rounding
+ * difference would flip first); for K = 1 that is z_i + tau_{0,i}. */
 void orc_quantize(const double *z, uint64_t n, uint64_t i0, double lam, uint32_t K,
                   uint32_t dither, uint64_t seed, uint64_t round, uint32_t party, int32_t *q,
                   double *margin)
@@ -210,7 +211,7 @@ void orc_quantize(const double *z, uint64_t n, uint64_t i0, double lam, uint32_t
             double tau = 0.0;
             if (dither == ORC_DITHER_UNIFORM) tau = lam * orc_dither_u(seed, round, party, k, i0 + l);
             double t = z[l] + tau;
-            if (k == 0 && margin) margin[l] = t;
+            if (margin && (k == 0 || fabs(t) < fabs(margin[l]))) margin[l] = t;
             s += (t >= 0.0) ? 1 : -1;
         }
         q[l] = s;

@@ -22,7 +22,7 @@ FORCE_SCALE = 1
 MAX_WORKERS = 64
 
 EXPORTS = ("fo_plan_create", "fo_plan_destroy", "fo_padded_len", "fo_packed_words", "fo_num_scales",
-           "fo_block_len", "fo_scratch_bytes", "fo_last_hip_error", "fo_encode", "fo_decode",
+           "fo_block_len", "fo_downlink_planes", "fo_scratch_bytes", "fo_last_hip_error", "fo_encode", "fo_decode",
            "fo_server_aggregate", "fo_step", "fo_step_messages", "fo_profile_begin", "fo_profile_end")
 
 
@@ -61,7 +61,8 @@ def load_library():
         lib.fo_plan_create.argtypes = [C.POINTER(Params), C.POINTER(vp)]
         lib.fo_plan_destroy.argtypes = [vp]
         lib.fo_plan_destroy.restype = None
-        for f in ("fo_padded_len", "fo_packed_words", "fo_num_scales", "fo_block_len", "fo_scratch_bytes"):
+        for f in ("fo_padded_len", "fo_packed_words", "fo_num_scales", "fo_block_len", "fo_downlink_planes",
+                  "fo_scratch_bytes"):
             getattr(lib, f).argtypes = [vp]
             getattr(lib, f).restype = C.c_size_t
         lib.fo_last_hip_error.restype = C.c_char_p
@@ -110,6 +111,7 @@ class Plan:
         self.W = lib.fo_packed_words(h)
         self.nblocks = lib.fo_num_scales(h)
         self.b = lib.fo_block_len(h)
+        self.planes = lib.fo_downlink_planes(h)
         self.scratch_bytes = lib.fo_scratch_bytes(h)
 
     def close(self):

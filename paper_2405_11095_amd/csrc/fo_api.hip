@@ -127,6 +127,7 @@ struct fo_plan {
     uint32_t S;          // stages done by the contiguous kernel
     uint32_t npass;      // strided passes: 0, 1 or 2
     uint32_t hb[2];      // stages of each strided pass (pass 0 is adjacent to the contiguous tile)
+    uint32_t planes;     // bit planes of the downlink message: ceil(log2(K + 1))
     float coef_lambda, sqrtb, rsqrtb, coef_s;
     // scratch (device)
     char *scratch;
@@ -137,7 +138,7 @@ struct fo_plan {
     float *partials;     // [M][ntiles]
     uint64_t *bits_up;   // [M][W]
     float *scales_up;    // [M][nblocks]
-    uint64_t *bits_down; // [W]
+    uint64_t *bits_down; // [planes][W]
     float *scales_down;  // [nblocks]
     Profiler prof;
 };
@@ -151,7 +152,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     const fo_params &q = *params;
     if (q.d < 1 || q.M < 1 || q.M > FO_MAX_WORKERS) return FO_EINVAL;
     if (q.block_log2 != 0 && (q.block_log2 < 6 || q.block_log2 > 30)) return FO_EINVAL;
-    if (q.K != 1) return FO_EINVAL;
+    if (q.K < 1 || q.K > FO_MAX_K) return FO_EINVAL;
     if (q.dither != FO_DITHER_UNIFORM && q.dither != FO_DITHER_NONE) return FO_EINVAL;
     if (q.scale_rule != FO_SCALE_BOUND && q.scale_rule != FO_SCALE_L2) return FO_EINVAL;
     if (q.eps_mode != FO_EPS_INDEPENDENT && q.eps_mode != FO_EPS_SHARED_WORKERS) return FO_EINVAL;
@@ -182,6 +183,10 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     pl->hb[0] = pl->npass == 2 ? (high + 1) / 2 : high;
     pl->hb[1] = high - pl->hb[0];
     if (q.eps_mode == FO_EPS_SHARED_WORKERS && pl->npass == 2) { delete pl; return FO_EINVAL; } // not built for b > 2^25
+    pl->planes = 0;
+    while ((q.K >> pl->planes) != 0) ++pl->planes;
+    // the decode side carries K b / 2 at most in int32 between its passes
+    if (q.K > 1 && pl->npass > 0 && (uint64_t)q.K * (pl->b / 2) >= ((uint64_t)1 << 31)) { delete pl; return FO_EINVAL; }
     const double bd = (double)pl->b;
     pl->coef_lambda = (float)((double)q.alpha * std::sqrt(std::log(bd) / bd));
     pl->sqrtb = (float)std::sqrt(bd);
@@ -194,7 +199,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     const size_t sz_c = pl->npass == 2 ? up(pl->ntot * 4) : 0;
     const size_t sz_part = up((size_t)q.M * pl->ntiles * 4);
     const size_t sz_bu = up((size_t)q.M * pl->W * 8), sz_su = up((size_t)q.M * pl->nblocks * 4);
-    const size_t sz_bd = up(pl->W * 8), sz_sd = up(pl->nblocks * 4);
+    const size_t sz_bd = up((size_t)pl->planes * pl->W * 8), sz_sd = up(pl->nblocks * 4);
     pl->scratch_bytes = sz_a + sz_b + sz_c + sz_part + sz_bu + sz_su + sz_bd + sz_sd;
     void *mem = nullptr;
     hipError_t e = hipMalloc(&mem, pl->scratch_bytes);
@@ -232,6 +237,7 @@ extern "C" size_t fo_padded_len(const fo_plan *p) { return p ? p->ntot : 0; }
 extern "C" size_t fo_packed_words(const fo_plan *p) { return p ? p->W : 0; }
 extern "C" size_t fo_num_scales(const fo_plan *p) { return p ? p->nblocks : 0; }
 extern "C" size_t fo_block_len(const fo_plan *p) { return p ? p->b : 0; }
+extern "C" size_t fo_downlink_planes(const fo_plan *p) { return p ? p->planes : 0; }
 extern "C" size_t fo_scratch_bytes(const fo_plan *p) { return p ? p->scratch_bytes : 0; }
 
 // ---------------------------------------------------------------------------------------------
@@ -310,6 +316,11 @@ int launch_pack(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigArg
 {
     const bool dither = c.dither == FO_DITHER_UNIFORM, small = c.S < 8;
     const dim3 block(kThreads);
+    if (c.K > 1) { // the K-fold quantiser of the server's message
+        if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true, 0, true>, grid, block, st, c, tab);
+        if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 0, true>, grid, block, st, c, tab);
+        return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, true>, grid, block, st, c, tab);
+    }
     if (dither && c.S == 15) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 15>, grid, block, st, c, tab);
     if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true>, grid, block, st, c, tab);
     if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false>, grid, block, st, c, tab);
@@ -341,7 +352,14 @@ ContigArgs contig_base(const fo_plan *pl, const Rng &r)
     c.coef_lambda = pl->coef_lambda;
     c.sqrtb = pl->sqrtb;
     c.len_in = c.len_out = pl->ntot;
+    c.K = 1; c.planes = 1;
     return c;
+}
+// Messages of the server carry the K-fold quantiser's counts (Def. 3.2); workers' messages are plain signs.
+void set_quantiser(ContigArgs &c, const fo_plan *pl, uint32_t party)
+{
+    c.K = party == FO_PARTY_SERVER ? pl->p.K : 1u;
+    c.planes = party == FO_PARTY_SERVER ? pl->planes : 1u;
 }
 
 constexpr uint32_t kPartyAllWorkers = 0xFFFFFFFEu;
@@ -370,6 +388,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     c.dst = bits; c.dst_stride = bits_stride;
     c.scales = scales; c.scales_stride = scales_stride;
     c.party0 = party0; c.eps_party0 = eps_party_of(pl, party0);
+    set_quantiser(c, pl, party0);
     const dim3 cgrid((unsigned)((pl->nblocks + 255) / 256));
     if (pl->npass == 0) {
         c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
@@ -422,11 +441,14 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     c.src = bits; c.src_stride = 0;
     c.scales = const_cast<float *>(scales); c.scales_stride = 0;
     c.party0 = party; c.eps_party0 = eps_party_of(pl, party);
-    // the decode-side transforms carry every value divided by two (see fo_contig.h)
-    out_coef *= 2.f;
+    set_quantiser(c, pl, party);
+    const bool multik = c.K > 1;
+    // the decode-side transforms carry every value divided by two (see fo_contig.h); D = (lambda / K) D_eps H^T q
+    out_coef *= 2.f / (float)c.K;
     if (pl->npass == 0) {
         c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
-        if (c.S == 15) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 15>), grid, block, st, c, none));
+        if (multik) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 0, true>), grid, block, st, c, none));
+        else if (c.S == 15) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 15>), grid, block, st, c, none));
         else FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32>), grid, block, st, c, none));
         return FO_OK;
     }
@@ -434,14 +456,20 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     StridedArgs s = strided_base(pl, r, pl->npass - 1);
     s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
     s.scales = scales; s.scales_stride = 0; s.eps_party0 = eps_party_of(pl, party);
-    if (pl->npass == 1) {
+    if (pl->npass == 1 && !multik) {
         // int16 intermediate between the two passes
         FO_TRY(launch(pl, KID_DEC_LOW, k_declow, grid, block, st, c));
         s.src = tmp;
         FO_TRY((launch_strided<SM_DEC_LAST, true>(pl, KID_DEC_HIGH, grid, st, s, none)));
         return FO_OK;
     }
-    FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), grid, block, st, c, none));
+    if (multik) FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15, true>), grid, block, st, c, none));
+    else FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), grid, block, st, c, none));
+    if (pl->npass == 1) {
+        s.src = tmp;
+        FO_TRY(launch_strided<SM_DEC_LAST>(pl, KID_DEC_HIGH, grid, st, s, none));
+        return FO_OK;
+    }
     StridedArgs s1 = strided_base(pl, r, 0);
     s1.src = tmp; s1.dst = pl->buf_c;
     FO_TRY(launch_strided<SM_MID_I32>(pl, KID_DEC_MID, grid, st, s1, none));
@@ -487,6 +515,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         e.src = pl->buf_b; e.dst = bits_down;
         e.scales = scales_down;
         e.party0 = FO_PARTY_SERVER; e.eps_party0 = FO_PARTY_SERVER;
+        set_quantiser(e, pl, FO_PARTY_SERVER);
         FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid1, st, e, none));
         return FO_OK;
     }
@@ -535,6 +564,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         c.dst = bits_down; c.dst_stride = 0;
         c.scales = scales_down; c.scales_stride = 0;
         c.party0 = FO_PARTY_SERVER; c.eps_party0 = FO_PARTY_SERVER;
+        set_quantiser(c, pl, FO_PARTY_SERVER);
         FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, dim3((unsigned)pl->ntiles, 1), st, c, none));
     }
     return FO_OK;

@@ -51,6 +51,8 @@ struct ContigArgs {
     uint32_t dither;        // 0 uniform, 1 none
     uint32_t store_mode;    // OUT_F32: STORE_*
     uint32_t M;             // IN_COUNT: number of packed vectors to add up
+    uint32_t K;             // MULTIK: averaging count of the quantiser (Def. 3.2) being applied / decoded
+    uint32_t planes;        // MULTIK: bit planes of the message, ceil(log2(K + 1)); plane p starts at word p * W
     uint32_t scales_only;   // IN_GRAD: write the blocks' amplitudes and stop (no transform)
     uint32_t party0;        // party id of slot 0 (slot y is party0 + y); FO_PARTY_SERVER stays as is
     uint32_t eps_party0;    // same for the eps stream
@@ -66,7 +68,11 @@ struct ContigArgs {
 // per-value code is branch free.
 // SC > 0: compiled for exactly SC stages inside the tile (SC = 15: transform length >= 2^15), which
 // makes every stage unconditional; SC = 0 reads the stage count from the arguments.
-template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0>
+// MULTIK: the K-fold averaged quantiser of Def. 3.2 (the server's message when K > 1).  Coordinate i carries
+// c_i = #{k < K : z_i + tau_{k,i} >= 0} in {0..K}, i.e. q_i = 2 c_i - K = (K / lambda) Q_{lambda,K}(z)_i, stored as
+// `planes` bit planes of W words each (plane p holds bit p of every c_i).  OUT_PACK draws K dithers per
+// coordinate and writes the planes; IN_BITS reads them.  K = 1 is the plain sign message and uses MULTIK = false.
+template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false>
 __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
 {
     using T = typename std::conditional<(IN == IN_BITS || IN == IN_COUNT), int32_t, float>::type;
@@ -131,13 +137,27 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
             const uint64_t gw = (uint64_t)tile * 512u + wave * 64u + c * 4u + (lane >> 4);
-            const uint64_t w = (gw < a.W) ? src[gw] : 0ull;
-            const uint32_t nib = (uint32_t)(w >> ((lane & 15u) * 4u));
-            // half of the b0 butterfly of the +-1 values (2 c - 1): sum / 2 = c0 + c1 - 1, difference / 2 = c0 - c1
-            const int32_t c0 = nib & 1u, c1 = (nib >> 1) & 1u, c2 = (nib >> 2) & 1u, c3 = (nib >> 3) & 1u;
-            v[4 * c + 0] = c0 + c1 - 1;
+            // half of the b0 butterfly of the values 2 c - K: sum / 2 = c0 + c1 - K, difference / 2 = c0 - c1
+            int32_t c0, c1, c2, c3, K = 1;
+            if constexpr (MULTIK) {
+                c0 = c1 = c2 = c3 = 0;
+                K = (int32_t)a.K;
+                for (uint32_t p = 0; p < a.planes; ++p) {
+                    const uint64_t w = (gw < a.W) ? src[p * a.W + gw] : 0ull;
+                    const uint32_t nib = (uint32_t)(w >> ((lane & 15u) * 4u));
+                    c0 += (int32_t)((nib & 1u) << p);
+                    c1 += (int32_t)(((nib >> 1) & 1u) << p);
+                    c2 += (int32_t)(((nib >> 2) & 1u) << p);
+                    c3 += (int32_t)(((nib >> 3) & 1u) << p);
+                }
+            } else {
+                const uint64_t w = (gw < a.W) ? src[gw] : 0ull;
+                const uint32_t nib = (uint32_t)(w >> ((lane & 15u) * 4u));
+                c0 = nib & 1u, c1 = (nib >> 1) & 1u, c2 = (nib >> 2) & 1u, c3 = (nib >> 3) & 1u;
+            }
+            v[4 * c + 0] = c0 + c1 - K;
             v[4 * c + 1] = c0 - c1;
-            v[4 * c + 2] = c2 + c3 - 1;
+            v[4 * c + 2] = c2 + c3 - K;
             v[4 * c + 3] = c2 - c3;
         }
     }
@@ -316,7 +336,61 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
     };
 
     // ------------------------------------------------------------------ output
-    if constexpr (OUT == OUT_PACK) {
+    if constexpr (OUT == OUT_PACK && MULTIK) {
+        uint32_t lo[8], hi[8]; // lane j: word of register j, one pair per bit plane
+#pragma unroll
+        for (int p = 0; p < 8; ++p) lo[p] = hi[p] = 0u;
+        const float tscale = a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m * 2^-24 with m odd
+        static_for<16>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            const uint32_t lg = local_of(2 * g); // b6 = b7 = 0
+            float thr_g = 0.f;
+            if constexpr (DITHER && !SMALLB) thr_g = lam[lg >> S] * tscale;
+            uint32_t cnt[4] = { 0u, 0u, 0u, 0u };
+            for (uint32_t k = 0; k < a.K; ++k) {
+                uint32_t w[4] = { 0u, 0u, 0u, 0u };
+                if constexpr (DITHER) {
+                    const RngKey key_k = { key_dit.k0, key_dit.k1, kDomainDither | (k << 8), key_dit.c2, key_dit.c3 };
+                    philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_k, w);
+                }
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int r = 2 * g + (s & 1) + 32 * (s >> 1); // slot s = b6 | b7 << 1
+                    float tv = v[r];
+                    if constexpr (DITHER) {
+                        float thr = thr_g;
+                        if constexpr (SMALLB) thr = lam[local_of(r) >> S] * tscale;
+                        const float m = fmaf((float)(w[s] >> 8), 2.f, -16777215.f);
+                        tv = fmaf(thr, m, tv);
+                    }
+                    cnt[s] += (tv >= 0.f) ? 1u : 0u;
+                }
+            }
+            static_for<8>([&](auto pc) {
+                constexpr int p = decltype(pc)::value;
+                if ((uint32_t)p < a.planes) {
+                    uint64_t word[4];
+#pragma unroll
+                    for (int s = 0; s < 4; ++s) word[s] = __ballot(((cnt[s] >> p) & 1u) != 0u);
+                    settle_ballots(word[0], word[1], word[2], word[3]);
+                    static_for<4>([&](auto sc) {
+                        constexpr int s = decltype(sc)::value;
+                        constexpr int r = 2 * g + (s & 1) + 32 * (s >> 1);
+                        lo[p] = write_lane<r>(lo[p], (uint32_t)word[s]);
+                        hi[p] = write_lane<r>(hi[p], (uint32_t)(word[s] >> 32));
+                    });
+                }
+            });
+        });
+        const uint64_t gw = (uint64_t)tile * 512u +
+                            ((lane & 1u) | ((lane >> 5) << 1) | (((lane >> 1) & 1u) << 2) | (wave << 3) | (((lane >> 2) & 7u) << 6));
+        if (gw < a.W) {
+            uint64_t *dst = static_cast<uint64_t *>(a.dst) + slot * a.dst_stride + gw;
+#pragma unroll
+            for (int p = 0; p < 8; ++p)
+                if ((uint32_t)p < a.planes) dst[(uint64_t)p * a.W] = ((uint64_t)hi[p] << 32) | lo[p];
+        }
+    } else if constexpr (OUT == OUT_PACK) {
         uint32_t my_lo = 0u, my_hi = 0u;
         const float tscale = a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m * 2^-24 with m odd
         static_for<16>([&](auto gc) {

@@ -40,19 +40,39 @@ def compare_bits(gpu_bits, margin, lam, b):
     return int(np.count_nonzero(diff & ~exempt)), int(np.count_nonzero(exempt)), int(np.count_nonzero(diff))
 
 
+def planes_to_code(planes, n, K):
+    """Bit planes [P][W] of the counts c_i -> the code q_i = 2 c_i - K (Def. 3.2 scaled by K / lambda)."""
+    planes = np.ascontiguousarray(planes, dtype=np.uint64).reshape(-1, n // 64)
+    c = np.zeros(n, dtype=np.int64)
+    for p in range(planes.shape[0]):
+        c += bits_to_bool(planes[p], n).astype(np.int64) << p
+    return (2 * c - K).astype(np.int32)
+
+
+def compare_codes(q_gpu, q_oracle, margin, lam, b):
+    """As compare_bits, for K >= 1: margin is the pre-quantisation value closest to zero over the K dithers."""
+    n = margin.size
+    lam_c = np.repeat(np.asarray(lam, dtype=np.float64), b)[:n]
+    exempt = np.abs(margin) < TIE * lam_c
+    diff = np.asarray(q_gpu) != np.asarray(q_oracle)
+    return int(np.count_nonzero(diff & ~exempt)), int(np.count_nonzero(exempt)), int(np.count_nonzero(diff))
+
+
 def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha=2.0, alpha_s=2.0,
-                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True, eps_mode=0, x0=None):
+                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True, eps_mode=0, x0=None, K=1):
     """Runs encode x M, server, decode and fo_step on the GPU and compares every stage with the
     oracle.  Returns a report dict; asserts nothing (callers apply the gates)."""
     import torch
 
-    plan = B.Plan(d=d, M=M, block_log2=block_log2, dither=dither, scale_rule=scale_rule, alpha=alpha,
+    plan = B.Plan(d=d, M=M, block_log2=block_log2, K=K, dither=dither, scale_rule=scale_rule, alpha=alpha,
                   alpha_s=alpha_s, B=Bnorm, seed=seed, eps_mode=eps_mode)
-    p = O.params(d=d, M=M, block_log2=block_log2, dither=dither, scale_rule=scale_rule, alpha=alpha,
+    p = O.params(d=d, M=M, block_log2=block_log2, K=K, dither=dither, scale_rule=scale_rule, alpha=alpha,
                  alpha_s=alpha_s, B=Bnorm, seed=seed, eps_mode=eps_mode)
     b, nb, nt = O.geometry(p)
     assert (plan.b, plan.nblocks, plan.ntot) == (b, nb, nt)
     W = nt // 64
+    PL = plan.planes
+    assert PL == max(1, int(K).bit_length())
     gd = [torch.from_numpy(g).to(device) for g in gs]
     bits_up = torch.zeros((M, W), dtype=torch.int64, device=device)
     lam_up = torch.zeros((M, nb), dtype=torch.float32, device=device)
@@ -65,7 +85,7 @@ def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha
         lam_up[:] = lam_up.max(dim=0, keepdim=True).values.expand(M, nb)
         for m in range(M):
             plan.fo_encode(gd[m], rnd, m, bits_up[m], lam_up[m], flags=B.FORCE_SCALE)
-    bits_down = torch.zeros(W, dtype=torch.int64, device=device)
+    bits_down = torch.zeros((PL, W), dtype=torch.int64, device=device)
     lam_s = torch.zeros(nb, dtype=torch.float32, device=device)
     gbar = torch.zeros(nt, dtype=torch.float32, device=device)
     plan.fo_server_aggregate(bits_up, lam_up, rnd, bits_down, lam_s, gbar)
@@ -104,11 +124,13 @@ def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha
     rep["lam_s_rel_err"] = float(np.max(np.abs(h_lam_s - free_s) / den))
     s = O.server(p, h_bits_up, h_lam_up.astype(np.float64), rnd, lam_s=h_lam_s.astype(np.float64), want_margin=True)
     rep["gbar_rel_l2"] = rel_l2(h_gbar, s["gbar"])
-    bad, exempt, raw = compare_bits(h_bits_down, s["margin"], h_lam_s, b)
+    q_gpu = planes_to_code(h_bits_down, nt, K)
+    assert q_gpu.min() >= -K and q_gpu.max() <= K
+    bad, exempt, raw = compare_codes(q_gpu, s["q_down"], s["margin"], h_lam_s, b)
     rep["downlink_mismatch"], rep["downlink_exempt"], rep["downlink_raw_diff"] = bad, exempt, raw
 
     # ---- stage (iii): worker decode of the GPU's downlink message
-    dec = O.decode(p, O.unpack(h_bits_down, nt), h_lam_s.astype(np.float64), rnd, SERVER)[:d]
+    dec = O.decode(p, q_gpu, h_lam_s.astype(np.float64), rnd, SERVER, K=K)[:d]
     rep["decode_rel_l2"] = rel_l2(h_out, dec)
 
     # ---- fo_step: same messages as the calls made by hand, and the SGD update
@@ -121,7 +143,7 @@ def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha
         pb_up, ps_up, pb_dn, ps_dn = plan.fo_step_messages()
         step_bits_up = _peek(torch, pb_up, M * W, torch.int64, device).view(np.uint64).reshape(M, W)
         step_lam_up = _peek(torch, ps_up, M * nb, torch.float32, device).reshape(M, nb)
-        step_bits_dn = _peek(torch, pb_dn, W, torch.int64, device).view(np.uint64)
+        step_bits_dn = _peek(torch, pb_dn, PL * W, torch.int64, device).view(np.uint64).reshape(PL, W)
         step_lam_s = _peek(torch, ps_dn, nb, torch.float32, device)
         rep["step_messages_equal"] = bool(
             np.array_equal(step_bits_up, h_bits_up) and np.array_equal(step_lam_up, h_lam_up)

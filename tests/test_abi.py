@@ -46,7 +46,8 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(d=0) == B.EINVAL
     assert create(M=0) == B.EINVAL and create(M=65) == B.EINVAL
     assert create(block_log2=5) == B.EINVAL and create(block_log2=31) == B.EINVAL
-    assert create(K=2) == B.EINVAL
+    assert create(K=0) == B.EINVAL and create(K=256) == B.EINVAL
+    assert create(K=200, d=1 << 25) == B.EINVAL  # K b / 2 would not fit the int32 intermediate
     assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=2) == B.EINVAL
     assert create(alpha=1.5) == B.EINVAL and create(alpha_s=float("nan")) == B.EINVAL
     assert create(scale_rule=0, B=0.0) == B.EINVAL

@@ -1,0 +1,87 @@
+"""K-fold averaged downlink quantiser (Def. 3.2 with K > 1; Sec. 4, "Server-to-workers encoding") on the GPU:
+whole rounds against the oracle stage by stage, the server-party encode on its own, and the 1/K law of the
+quantiser's second moment (Lemma "Second moment of the quantizer") measured on the GPU's own output."""
+import numpy as np
+import pytest
+
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+SERVER = 0xFFFFFFFF
+
+
+@pytest.fixture(scope="module")
+def env(oracle):
+    import torch
+    from paper_2405_11095_amd import binding as B, inputs
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return oracle, B, inputs, torch.device("cuda:0")
+
+
+@pytest.mark.parametrize("name,d,M,blk,K,kw", [
+    ("single_pass_K2", 20_000, 3, 0, 2, {}),
+    ("two_pass_K3", 100_000, 3, 0, 3, {}),
+    ("small_blocks_K5", 5_000, 2, 7, 5, {}),
+    ("blocks_4096_K8", 300_000, 2, 12, 8, {}),
+    ("eight_planes_K255", 70_000, 2, 0, 255, {}),
+    ("no_dither_K3", 40_000, 2, 0, 3, dict(dither=1)),
+    ("three_pass_K3", (1 << 25) + 5, 1, 0, 3, {}),
+])
+def test_round_trip_with_averaged_downlink(env, name, d, M, blk, K, kw):
+    O, B, inputs, dev = env
+    gs = [inputs.gaussian(d, m) for m in range(M)]
+    rep = P.check_round_trip(O, B, gs, d, M, blk, seed=0xF05D + 40 + K, rnd=6, delta=1e-3, device=dev, K=K, **kw)
+    print(name, rep)
+    P.gates(rep)
+
+
+@pytest.mark.parametrize("d,blk,K", [(50_000, 0, 4), (9_000, 8, 6)])
+def test_server_party_encode_and_decode(env, d, blk, K):
+    """fo_encode / fo_decode for the server party use the K-fold quantiser on their own as well."""
+    import torch
+    O, B, inputs, dev = env
+    plan = B.Plan(d=d, M=1, block_log2=blk, K=K, seed=77)
+    p = O.params(d=d, M=1, block_log2=blk, K=K, seed=77)
+    b, nb, nt = O.geometry(p)
+    x = np.zeros(nt, dtype=np.float32)
+    x[:d] = inputs.gaussian(d, 1)
+    planes = torch.zeros((plan.planes, plan.W), dtype=torch.int64, device=dev)
+    lam = torch.zeros(nb, dtype=torch.float32, device=dev)
+    plan.fo_encode(torch.from_numpy(x).to(dev), 3, SERVER, planes, lam)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan.fo_decode(planes, lam, 3, SERVER, out)
+    torch.cuda.synchronize()
+    h_lam = lam.cpu().numpy()
+    r = O.encode(p, x[:d].astype(np.float64), 3, SERVER, K=K, lam=h_lam.astype(np.float64), want_margin=True)
+    q_gpu = P.planes_to_code(planes.cpu().numpy().view(np.uint64), nt, K)
+    bad, exempt, raw = P.compare_codes(q_gpu, r["q"], r["margin"], h_lam, b)
+    assert bad == 0, (bad, exempt, raw)
+    dec = O.decode(p, q_gpu, h_lam.astype(np.float64), 3, SERVER, K=K)[:d]
+    assert P.rel_l2(out.cpu().numpy(), dec) <= 1e-5
+    plan.close()
+
+
+def test_second_moment_falls_as_one_over_K(env):
+    """E ||Z_{lambda,K}(x) - x||^2 = (lambda^2 n - ||x||^2) / K when ||H_eps x||_inf <= lambda: measured on the GPU
+    for K = 1, 4, 16 over a few rounds (n = 2^16 coordinates average the dither well)."""
+    import torch
+    O, B, inputs, dev = env
+    d = 1 << 16
+    x = inputs.gaussian(d, 2)
+    xd = torch.from_numpy(x).to(dev)
+    nx2 = float(np.sum(x.astype(np.float64) ** 2))
+    for K in (1, 4, 16):
+        plan = B.Plan(d=d, M=1, K=K, seed=123)
+        planes = torch.zeros((plan.planes, plan.W), dtype=torch.int64, device=dev)
+        lam = torch.zeros(1, dtype=torch.float32, device=dev)
+        out = torch.zeros(d, dtype=torch.float32, device=dev)
+        errs = []
+        for rnd in range(8):
+            plan.fo_encode(xd, rnd, SERVER, planes, lam)
+            plan.fo_decode(planes, lam, rnd, SERVER, out)
+            errs.append(float(((out - xd).double() ** 2).sum()))
+        l = float(lam[0])
+        want = (l * l * d - nx2) / K
+        got = float(np.mean(errs))
+        assert abs(got - want) <= 0.02 * want, (K, got, want)
+        plan.close()
