@@ -38,7 +38,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4"],
+                    help="c3 is the headline workload; the others are the parity configurations, timed for the report")
+    ap.add_argument("--block-log2", type=int, default=None,
+                    help="transform length 2^k (default: the workload's first entry; c4 has 10, 12, 14, 16)")
+    ap.add_argument("--K", type=int, default=1, help="averaging count of the downlink quantiser")
     ap.add_argument("--eps-mode", default="independent", choices=["independent", "shared"],
                     help="independent: the paper's protocol (default, the headline number); shared: one eps for all "
                          "workers and the popcount server")
@@ -65,7 +69,9 @@ def main():
     gs = [torch.from_numpy(g).to(dev) for g in gs_host]
     x = torch.zeros(d, dtype=torch.float32, device=dev)
     eps_mode = B.EPS_SHARED_WORKERS if args.eps_mode == "shared" else B.EPS_INDEPENDENT
-    plan = B.Plan(d=d, M=M, block_log2=0, seed=0xF05D + 3, eps_mode=eps_mode)
+    blk = wl["block_log2"][0] if args.block_log2 is None else args.block_log2
+    seed = 0xF05D + int(args.workload[1])
+    plan = B.Plan(d=d, M=M, block_log2=blk, K=args.K, seed=seed, eps_mode=eps_mode)
     n = plan.ntot
     print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "
           f"plan scratch {plan.scratch_bytes / 2**30:.2f} GiB", file=sys.stderr, flush=True)
@@ -104,6 +110,7 @@ def main():
         "k_declow": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
+        "k_server_tile": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
         "k_contig<IN_BITS,OUT_F32>": M * (W8 + 8 * n) + (W8 + 8 * d),
@@ -114,7 +121,7 @@ def main():
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None,
-        "traffic": MEASURED_TRAFFIC.get(dom) if (args.workload == "c3" and args.eps_mode == "independent") else None,
+        "traffic": MEASURED_TRAFFIC.get(dom) if (args.workload == "c3" and args.eps_mode == "independent" and args.K == 1) else None,
         "avg_launch_ms": round(avg_ms, 4), "bytes_per_launch": bytes_per_launch,
         "kernel_ms_per_step": {k: round(ms / args.steps, 4) for k, (l, ms) in sorted(per_kernel.items())},
         "step_model_bytes": sum(v for k, v in per_step.items() if k in per_kernel),
@@ -126,7 +133,7 @@ def main():
         from oracle import fo_oracle as O
         Ms = min(8, M)                                   # bounded sample: the first Ms workers, full d
         nthreads = max(1, min(Ms, 16, os.cpu_count() or 1))
-        p = O.params(d=d, M=Ms, block_log2=0, seed=0xF05D + 3, eps_mode=1 if args.eps_mode == "shared" else 0)
+        p = O.params(d=d, M=Ms, block_log2=blk, K=args.K, seed=seed, eps_mode=1 if args.eps_mode == "shared" else 0)
         xo = np.zeros(d, dtype=np.float64)
         c0 = time.perf_counter()
         O.round_trip(p, gs_host[:Ms], xo, delta, 0, nthreads=nthreads)
@@ -141,9 +148,10 @@ def main():
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: d={d} fp32 padded to n={n}, M={M} workers, full-length randomized FWHT, "
-                               f"uniform dither, L2 scale rule, alpha=alpha_s=2, {args.eps_mode} eps, one fo_step per step",
-                   "d": d, "n": n, "M": M, "block_log2": 0},
+        "config": {"workload": f"{args.workload}: d={d} fp32 padded to n={n}, M={M} workers, "
+                               f"{'full-length' if blk == 0 else f'blocks of 2^{blk}'} randomized FWHT, uniform dither, "
+                               f"L2 scale rule, alpha=alpha_s=2, K={args.K}, {args.eps_mode} eps, one fo_step per step",
+                   "d": d, "n": n, "M": M, "block_log2": blk},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -72,18 +72,18 @@ struct ContigArgs {
 // c_i = #{k < K : z_i + tau_{k,i} >= 0} in {0..K}, i.e. q_i = 2 c_i - K = (K / lambda) Q_{lambda,K}(z)_i, stored as
 // `planes` bit planes of W words each (plane p holds bit p of every c_i).  OUT_PACK draws K dithers per
 // coordinate and writes the planes; IN_BITS reads them.  K = 1 is the plain sign message and uses MULTIK = false.
-template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false>
-__global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
+// The work of one workgroup on tile `tile` of party slot `slot`; lds has kLdsWords words.
+template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK>
+__device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &tab, const uint32_t tile, const uint32_t slot,
+                                            uint32_t *const lds)
 {
     using T = typename std::conditional<(IN == IN_BITS || IN == IN_COUNT), int32_t, float>::type;
-    __shared__ uint32_t lds[kLdsWords];
     uint32_t *const xbuf = lds;
     uint32_t *const epsw = lds + kXWords;
     float *const lam = reinterpret_cast<float *>(lds + kXWords + kEpsWords);
     float *const red = reinterpret_cast<float *>(lds + kXWords + kEpsWords + kLamWords);
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
     const uint64_t base = (uint64_t)tile << kTileLog2;
     const uint32_t S = SC ? (uint32_t)SC : a.S;
     const uint32_t party = (a.party0 == 0xFFFFFFFFu) ? a.party0 : a.party0 + slot;
@@ -459,6 +459,13 @@ __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, cons
             }
         }
     }
+}
+
+template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false>
+__global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
+{
+    __shared__ uint32_t lds[kLdsWords];
+    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK>(a, tab, blockIdx.x, blockIdx.y, lds);
 }
 
 } // namespace fo

@@ -34,30 +34,32 @@ constexpr uint32_t walsh_mask32(int j)
     return m;
 }
 
-// Uses src, src_stride (64-bit words between slots), dst, dst_stride (int16 elements between slots) and W
-// of the argument block; the transform length is at least 2^15, so every tile is complete.
-__global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
+// Decode-side stages of one tile from its 1024 packed 32-bit words, result in layout LC as 32 packed pairs.
+// SC = 15: all fifteen stages (transform length >= 2^15); SC = 0: the S = 6..15 stages of a blocked transform
+// (stage k runs iff k < S; the popcount stages b0..b4 always do).  words points at the party's packed vector.
+// xbuf: kXWords words of LDS.  Ends with the workgroup past a barrier, so xbuf may be reused at once.
+template <int SC>
+__device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xbuf,
+                                            s16x2 (&v)[32])
 {
-    __shared__ uint32_t xbuf[kXWords];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
-    const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
-
-    s16x2 v[32];
+    const uint32_t S = SC ? (uint32_t)SC : S_arg;
 
     // ------------------------------------------------------------------ stages b0..b4 (layout LA)
 #pragma unroll
     for (int x = 0; x < 2; ++x) {
         const uint64_t gh = (uint64_t)tile * 1024u + wave * 128u + x * 64u + lane; // 32-bit half word
-        const uint32_t w = (gh < 2 * a.W) ? src[gh] : 0u;
+        const uint32_t w = (gh < 2 * W) ? words[gh] : 0u;
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
             const uint32_t hi = (uint32_t)__builtin_popcount(w ^ walsh_mask32(2 * k + 1));
             const uint32_t both = (uint32_t)__builtin_popcount(w ^ walsh_mask32(2 * k)) + (hi << 16);
             v[x * 16 + k] = __builtin_bit_cast(s16x2, both);
+            // blocked transforms take the popcount's offset off here; the full-tile case does it at the end
+            if constexpr (SC == 0) v[x * 16 + k] -= (s16x2)(16, 16);
         }
     }
-    bfly<s16x2, 4, 32>(v); // b11
+    if (S > 11u) bfly<s16x2, 4, 32>(v); // b11
 
     // ------------------------------------------------------------------ exchange LA -> LB (inside each half wave)
     {
@@ -69,12 +71,12 @@ __global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
 #pragma unroll
         for (int r = 0; r < 32; ++r) v[r] = __builtin_bit_cast(s16x2, wb[col * 33 + r]);
     }
-    bfly<s16x2, 0, 32>(v);
-    bfly<s16x2, 1, 32>(v);
-    bfly<s16x2, 2, 32>(v);
-    bfly<s16x2, 3, 32>(v);
-    bfly<s16x2, 4, 32>(v);
-    bfly_lane5<s16x2, 32>(v); // b10
+    bfly<s16x2, 0, 32>(v); // b5: every transform has at least 2^6 points
+    if (S > 6u) bfly<s16x2, 1, 32>(v);
+    if (S > 7u) bfly<s16x2, 2, 32>(v);
+    if (S > 8u) bfly<s16x2, 3, 32>(v);
+    if (S > 9u) bfly<s16x2, 4, 32>(v);
+    if (S > 10u) bfly_lane5<s16x2, 32>(v); // b10
 
     // ------------------------------------------------------------------ exchange LB -> LC (whole workgroup)
     // Address = dword index D plus 16 words of padding per 1024: the writers' lanes spread over
@@ -93,20 +95,38 @@ __global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
         for (int r = 0; r < 32; ++r) // register r = (b12,b13,b14,b7,b8)
             v[r] = __builtin_bit_cast(s16x2, xbuf[rofs + ((r >> 3) & 1) * 64 + (r >> 4) * 128 + (r & 7) * (2048 + 32)]);
     }
-    bfly<s16x2, 0, 32>(v);
-    bfly<s16x2, 1, 32>(v);
-    bfly<s16x2, 2, 32>(v);
+    __syncthreads(); // the buffer is free again
+    if (S > 12u) bfly<s16x2, 0, 32>(v);
+    if (S > 13u) bfly<s16x2, 1, 32>(v);
+    if (S > 14u) bfly<s16x2, 2, 32>(v);
 
     // the popcount offset, gathered by the ten later stages on the coordinates with b5..b14 = 0
-    if (t < 16u) v[0] -= (s16x2)(16384, 16384);
+    if constexpr (SC == 15)
+        if (t < 16u) v[0] -= (s16x2)(16384, 16384);
+}
 
-    // ------------------------------------------------------------------ store: a wave writes 256 contiguous bytes per register
+// dword index (= coordinate / 2) inside the tile of register r of this thread in layout LC
+__device__ __forceinline__ constexpr uint32_t declow_reg_dword(int r)
+{
+    return ((uint32_t)((r >> 3) & 1) << 6) | ((uint32_t)(r >> 4) << 7) | ((uint32_t)(r & 7) << 11);
+}
+
+// Uses src, src_stride (64-bit words between slots), dst, dst_stride (int16 elements between slots) and W
+// of the argument block; the transform length is at least 2^15, so every tile is complete.
+__global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
+{
+    __shared__ uint32_t xbuf[kXWords];
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
+    s16x2 v[32];
+    declow_tile<15>(src, a.W, tile, 15u, xbuf, v);
+
+    // store: a wave writes 256 contiguous bytes per register
     uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<int16_t *>(a.dst) + slot * a.dst_stride + ((uint64_t)tile << kTileLog2));
+    const uint32_t dt = lane | (wave << 8);
 #pragma unroll
-    for (int r = 0; r < 32; ++r) {
-        const uint32_t di = lane | ((uint32_t)((r >> 3) & 1) << 6) | ((uint32_t)(r >> 4) << 7) | (wave << 8) | ((uint32_t)(r & 7) << 11);
-        dst[di] = __builtin_bit_cast(uint32_t, v[r]);
-    }
+    for (int r = 0; r < 32; ++r) dst[dt + declow_reg_dword(r)] = __builtin_bit_cast(uint32_t, v[r]);
 }
 
 } // namespace fo
