@@ -113,7 +113,7 @@ def main():
         "k_server_tile": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
-        "k_contig<IN_BITS,OUT_F32>": M * (W8 + 8 * n) + (W8 + 8 * d),
+        "k_decode_tile": W8 + 8 * d,
     }
     step_bytes = per_step.get(dom)
     bytes_per_launch = step_bytes * args.steps / launches if step_bytes else None

@@ -105,7 +105,7 @@ enum KernelId {
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
-    "k_contig<IN_BITS,OUT_F32>",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
+    "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
     "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_server_tile", "scale kernels",
 };
 
@@ -265,7 +265,10 @@ inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
     if (kid == KID_COUNT_LOW && (c.M < 1 || c.M > FO_MAX_WORKERS)) return false;
     return !needs_scales || c.scales != nullptr;
 }
-inline bool args_ok(const ContigArgs &c, int) { return c.src && c.dst; } // k_declow
+inline bool args_ok(const ContigArgs &c, int kid) // k_declow, k_decode_tile
+{
+    return c.src && c.dst && (kid != KID_DEC_SINGLE || (c.scales && c.S >= 6 && c.S <= 15));
+}
 inline bool args_ok(const ServerTileArgs &s, const PtrTab &, int)
 {
     return s.enc.src && s.enc.dst && s.enc.scales && s.bits_up && s.scales_up && s.M >= 1 && s.M <= FO_MAX_WORKERS &&
@@ -455,8 +458,7 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     if (pl->npass == 0) {
         c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
         if (multik) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 0, true>), grid, block, st, c, none));
-        else if (c.S == 15) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 15>), grid, block, st, c, none));
-        else FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32>), grid, block, st, c, none));
+        else FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile, grid, block, st, c));
         return FO_OK;
     }
     c.dst = tmp; c.dst_stride = 0;

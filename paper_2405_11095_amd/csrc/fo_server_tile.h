@@ -84,4 +84,62 @@ __global__ __launch_bounds__(kThreads, 2) void k_server_tile(const ServerTileArg
     contig_tile<IN_GRAD, OUT_PACK, DITHER, SMALLB, 0, MULTIK>(a, tab, tile, 0u, lds);
 }
 
+// Decoder of one party for transforms that fit a tile (Def. 3.8): out = lambda D_eps H^T q, first len_out
+// coordinates, stored / accumulated / applied as x -= delta * value (eq. "workers update").  Uses of the
+// argument block: src (packed signs), W, S, nblocks, scales (+ stride), eps_party0, the generator key,
+// dst, len_out, store_mode, out_coef (for half-valued integers), delta.
+__global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
+{
+    __shared__ uint32_t lds[kXWords + kEpsWords + kLamWords];
+    uint32_t *const xbuf = lds;
+    uint32_t *const epsw = lds + kXWords;
+    float *const lam = reinterpret_cast<float *>(lds + kXWords + kEpsWords);
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t tile = blockIdx.x, slot = blockIdx.y;
+    const uint32_t S = a.S;
+    const uint64_t base = (uint64_t)tile << kTileLog2;
+    const uint32_t nblk_tile = kTile >> S;
+    const uint32_t dt = lane | (wave << 8);
+    const uint32_t eshift = (lane & 15u) << 1;
+    const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
+
+    if (t < 256u) {
+        const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
+        uint32_t w[4];
+        philox((uint32_t)(base >> 7) + t, key_eps, w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) epsw[t * 4u + j] = w[j];
+    }
+    if (t < nblk_tile) {
+        const uint64_t gb = (uint64_t)tile * nblk_tile + t;
+        lam[t] = gb < a.nblocks ? a.scales[slot * a.scales_stride + gb] * a.out_coef : 0.f;
+    }
+    s16x2 v[32];
+    const uint32_t *words = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
+    declow_tile<0>(words, a.W, tile, S, xbuf, v); // its barriers publish the tables
+
+    float2 *dst = reinterpret_cast<float2 *>(static_cast<float *>(a.dst) + base);
+    const uint64_t room = a.len_out > base ? a.len_out - base : 0; // valid coordinates of this tile
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        const uint32_t D = dt + declow_reg_dword(r);
+        const uint32_t w = epsw[D >> 4];
+        const uint32_t cbits = __float_as_uint(lam[D >> (S - 1u)]);
+        const float y0 = (float)v[r].x * __uint_as_float(((w >> eshift) << 31) | cbits);
+        const float y1 = (float)v[r].y * __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits);
+        if (2ull * D + 1 < room) {
+            float2 q = dst[D];
+            if (a.store_mode == STORE_SET) q = make_float2(y0, y1);
+            else if (a.store_mode == STORE_ACC) q = make_float2(q.x + y0, q.y + y1);
+            else q = make_float2(q.x - a.delta * y0, q.y - a.delta * y1);
+            dst[D] = q;
+        } else if (2ull * D < room) {
+            float &q = static_cast<float *>(a.dst)[base + 2ull * D];
+            if (a.store_mode == STORE_SET) q = y0;
+            else if (a.store_mode == STORE_ACC) q += y0;
+            else q -= a.delta * y0;
+        }
+    }
+}
+
 } // namespace fo
