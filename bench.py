@@ -43,9 +43,9 @@ def main():
     ap.add_argument("--block-log2", type=int, default=None,
                     help="transform length 2^k (default: the workload's first entry; c4 has 10, 12, 14, 16)")
     ap.add_argument("--K", type=int, default=1, help="averaging count of the downlink quantiser")
-    ap.add_argument("--eps-mode", default="independent", choices=["independent", "shared"],
+    ap.add_argument("--eps-mode", default="independent", choices=["independent", "shared", "all"],
                     help="independent: the paper's protocol (default, the headline number); shared: one eps for all "
-                         "workers and the popcount server")
+                         "workers and the popcount server; all: the server shares that eps too and needs no transform")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic, used to scale "
@@ -68,7 +68,7 @@ def main():
     gs_host = inputs.workload(args.workload)
     gs = [torch.from_numpy(g).to(dev) for g in gs_host]
     x = torch.zeros(d, dtype=torch.float32, device=dev)
-    eps_mode = B.EPS_SHARED_WORKERS if args.eps_mode == "shared" else B.EPS_INDEPENDENT
+    eps_mode = {"independent": B.EPS_INDEPENDENT, "shared": B.EPS_SHARED_WORKERS, "all": B.EPS_SHARED_ALL}[args.eps_mode]
     blk = wl["block_log2"][0] if args.block_log2 is None else args.block_log2
     seed = 0xF05D + int(args.workload[1])
     plan = B.Plan(d=d, M=M, block_log2=blk, K=args.K, seed=seed, eps_mode=eps_mode)
@@ -111,6 +111,7 @@ def main():
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_server_tile": M * W8 + W8,
+        "k_shall": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
         "k_decode_tile": W8 + 8 * d,
@@ -133,7 +134,7 @@ def main():
         from oracle import fo_oracle as O
         Ms = min(8, M)                                   # bounded sample: the first Ms workers, full d
         nthreads = max(1, min(Ms, 16, os.cpu_count() or 1))
-        p = O.params(d=d, M=Ms, block_log2=blk, K=args.K, seed=seed, eps_mode=1 if args.eps_mode == "shared" else 0)
+        p = O.params(d=d, M=Ms, block_log2=blk, K=args.K, seed=seed, eps_mode=int(eps_mode))
         xo = np.zeros(d, dtype=np.float64)
         c0 = time.perf_counter()
         O.round_trip(p, gs_host[:Ms], xo, delta, 0, nthreads=nthreads)

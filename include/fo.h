@@ -43,6 +43,12 @@
  * workers' amplitudes); a caller driving fo_encode by hand must pass that amplitude with
  * FO_FORCE_SCALE, and fo_server_aggregate then reads worker 0's scales as everybody's.
  *
+ * FO_EPS_SHARED_ALL goes one step further and lets the server use the workers' eps too: then
+ * H D_eps gbar = (lambda / M)(2 c - M) and the server needs no transform at all, only the count, the dither
+ * and the comparison.  This drops the independence of eps^s that the paper's server lemma assumes; it is a
+ * flagged variant, never the default.  gbar_or_null still works (one inverse transform, for checking).
+ * Both shared modes are built for transform lengths up to 2^25.
+ *
  * Averaged downlink quantiser (K > 1).  The server's message is Q_{lambda^s,K} of Def. 3.2: the mean of K
  * one-bit quantisers with independent dithers, which cuts the downlink's error term by K (Lemma "Second
  * moment of the quantizer").  Coordinate i then carries the count c_i in {0..K} of dithers for which
@@ -79,6 +85,7 @@ extern "C" {
 #define FO_SCALE_L2 1u       /* B := measured ||g_block||_2 at this call                 */
 #define FO_EPS_INDEPENDENT 0u /* one eps per worker and one for the server (Sec. 4)     */
 #define FO_EPS_SHARED_WORKERS 1u /* one eps for all workers, an independent one for the server */
+#define FO_EPS_SHARED_ALL 2u /* one eps for the workers and the server (flagged variant, see above) */
 
 #define FO_PARTY_SERVER 0xFFFFFFFFu /* party id of the server; workers are 0 .. M-1      */
 #define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libfo.so")
 OK, EINVAL, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4
 DITHER_UNIFORM, DITHER_NONE = 0, 1
 SCALE_BOUND, SCALE_L2 = 0, 1
-EPS_INDEPENDENT, EPS_SHARED_WORKERS = 0, 1
+EPS_INDEPENDENT, EPS_SHARED_WORKERS, EPS_SHARED_ALL = 0, 1, 2
 PARTY_SERVER = 0xFFFFFFFF
 FORCE_SCALE = 1
 MAX_WORKERS = 64

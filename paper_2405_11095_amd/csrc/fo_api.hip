@@ -12,6 +12,7 @@
 #include "fo_strided.h"
 #include "fo_declow.h"
 #include "fo_server_tile.h"
+#include "fo_shall.h"
 
 using namespace fo;
 
@@ -100,13 +101,14 @@ enum KernelId {
     KID_SERVER_HIGH,    // k_strided<SERVER> / k_strided<SHARED>
     KID_COUNT_LOW,      // k_contig<IN_COUNT,*>
     KID_SERVER_TILE,    // k_server_tile
+    KID_SHALL,          // k_shall
     KID_SCALES,         // k_finalize_scales / k_fill_scales / k_server_scales
     KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_server_tile", "scale kernels",
+    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_server_tile", "k_shall", "scale kernels",
 };
 
 struct Profiler {
@@ -157,7 +159,8 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     if (q.K < 1 || q.K > FO_MAX_K) return FO_EINVAL;
     if (q.dither != FO_DITHER_UNIFORM && q.dither != FO_DITHER_NONE) return FO_EINVAL;
     if (q.scale_rule != FO_SCALE_BOUND && q.scale_rule != FO_SCALE_L2) return FO_EINVAL;
-    if (q.eps_mode != FO_EPS_INDEPENDENT && q.eps_mode != FO_EPS_SHARED_WORKERS) return FO_EINVAL;
+    if (q.eps_mode != FO_EPS_INDEPENDENT && q.eps_mode != FO_EPS_SHARED_WORKERS && q.eps_mode != FO_EPS_SHARED_ALL)
+        return FO_EINVAL;
     if (!(q.alpha >= 2.f) || !(q.alpha_s >= 2.f)) return FO_EINVAL;
     if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
 
@@ -184,7 +187,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     pl->npass = high == 0 ? 0 : (high <= 10 ? 1 : 2);
     pl->hb[0] = pl->npass == 2 ? (high + 1) / 2 : high;
     pl->hb[1] = high - pl->hb[0];
-    if (q.eps_mode == FO_EPS_SHARED_WORKERS && pl->npass == 2) { delete pl; return FO_EINVAL; } // not built for b > 2^25
+    if (q.eps_mode != FO_EPS_INDEPENDENT && pl->npass == 2) { delete pl; return FO_EINVAL; } // shared eps: not built for b > 2^25
     pl->planes = 0;
     while ((q.K >> pl->planes) != 0) ++pl->planes;
     // the decode side carries K b / 2 at most in int32 between its passes
@@ -268,6 +271,10 @@ inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
 inline bool args_ok(const ContigArgs &c, int kid) // k_declow, k_decode_tile
 {
     return c.src && c.dst && (kid != KID_DEC_SINGLE || (c.scales && c.S >= 6 && c.S <= 15));
+}
+inline bool args_ok(const ShallArgs &z, int)
+{
+    return z.bits_up && z.dst && z.lam && z.lam_s && z.M >= 1 && z.M <= FO_MAX_WORKERS && z.K >= 1 && z.planes >= 1;
 }
 inline bool args_ok(const ServerTileArgs &s, const PtrTab &, int)
 {
@@ -376,7 +383,8 @@ constexpr uint32_t kPartyAllWorkers = 0xFFFFFFFEu;
 // Which eps stream a party uses: its own, or the common one of the workers in shared-eps mode.
 uint32_t eps_party_of(const fo_plan *pl, uint32_t party)
 {
-    if (party == FO_PARTY_SERVER || pl->p.eps_mode == FO_EPS_INDEPENDENT) return party;
+    if (pl->p.eps_mode == FO_EPS_INDEPENDENT) return party;
+    if (party == FO_PARTY_SERVER && pl->p.eps_mode == FO_EPS_SHARED_WORKERS) return party;
     return kPartyAllWorkers;
 }
 
@@ -497,7 +505,18 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
     FO_TRY(launch(pl, KID_SCALES, k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), st, scales_up,
                        pl->nblocks, M, pl->coef_s, scales_down));
     const float mean_coef = pl->rsqrtb / (float)M;
-    if (pl->p.eps_mode == FO_EPS_SHARED_WORKERS && pl->npass <= 1) {
+    const bool zero_transform = pl->p.eps_mode == FO_EPS_SHARED_ALL;
+    if (zero_transform) {
+        // the server shares the workers' eps: its pre-quantisation vector is (lambda / M)(2 c - M), no transform
+        ShallArgs z;
+        z.bits_up = bits_up; z.dst = bits_down; z.lam = scales_up; z.lam_s = scales_down;
+        z.W = pl->W; z.logb = pl->logb; z.M = M; z.K = pl->p.K; z.planes = pl->planes; z.dither = pl->p.dither;
+        z.k0 = r.k0; z.k1 = r.k1; z.round_lo = r.round_lo; z.sqrtb = pl->sqrtb;
+        FO_TRY(launch(pl, KID_SHALL, k_shall, dim3((unsigned)((pl->W + 15) / 16)), dim3(256), st, z));
+        if (!gbar_or_null) return FO_OK;
+        // the mean itself was asked for (checking): one inverse transform of the summed sign vectors, below
+    }
+    if (pl->p.eps_mode != FO_EPS_INDEPENDENT && pl->npass <= 1) {
         // one eps and one amplitude for all workers: sum the packed sign vectors per coordinate (vertical
         // popcount), then a single inverse transform instead of M
         ContigArgs c = contig_base(pl, r);
@@ -509,6 +528,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
             float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
             c.dst = gbar; c.len_out = pl->ntot; c.store_mode = STORE_SET; c.out_coef = mean_coef;
             FO_TRY(launch(pl, KID_COUNT_LOW, (k_contig<IN_COUNT, OUT_F32>), grid1, block, st, c, none));
+            if (zero_transform) return FO_OK;
             return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down,
                                  0, nullptr, 0, st);
         }
@@ -520,6 +540,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.gbar = gbar_or_null;
         s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
         FO_TRY(launch_strided<SM_SHARED>(pl, KID_SERVER_HIGH, grid1, st, s, none));
+        if (zero_transform) return FO_OK;
         ContigArgs e = contig_base(pl, r);
         e.src = pl->buf_b; e.dst = bits_down;
         e.scales = scales_down;
@@ -664,7 +685,7 @@ extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta
                                pl->scales_up + (uint64_t)m * pl->nblocks, 0, pl->buf_a, 0, st);
     } else {
         rc = launch_encode(pl, &tab, nullptr, 0, pl->p.d, M, 0, round, given, pl->bits_up, pl->W, pl->scales_up,
-                           pl->nblocks, pl->buf_a, pl->ntot, st, pl->p.eps_mode == FO_EPS_SHARED_WORKERS);
+                           pl->nblocks, pl->buf_a, pl->ntot, st, pl->p.eps_mode != FO_EPS_INDEPENDENT);
     }
     if (rc) return rc;
     rc = launch_server(pl, pl->bits_up, pl->scales_up, round, pl->bits_down, pl->scales_down, nullptr, st);

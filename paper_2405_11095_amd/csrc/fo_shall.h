@@ -1,0 +1,75 @@
+// Server step when the server shares the workers' eps and all workers share one amplitude per block
+// (FO_EPS_SHARED_ALL, a variant the paper does not have).  The server's pre-quantisation vector is
+//   H D_eps gbar = H D_eps (lambda / M) D_eps H^T sum_n q_n = (lambda / M) sum_n q_n = (lambda / M)(2 c - M),
+// c_i the number of workers whose bit i is set: no transform at all, only a vertical count, the dither of
+// Def. 3.2 with amplitude lambda^s, the comparison and the packing (Sec. 4, "Server-to-workers encoding").
+// A wave handles 256 consecutive coordinates (four packed words): they share one generator call per lane.
+#pragma once
+#include "fo_device.h"
+
+namespace fo {
+
+struct ShallArgs {
+    const uint64_t *bits_up;   // [M][W]
+    uint64_t *dst;             // [planes][W]
+    const float *lam;          // [nblocks] the workers' common amplitude
+    const float *lam_s;        // [nblocks] the server's amplitude
+    uint64_t W;
+    uint32_t logb, M, K, planes, dither;
+    uint32_t k0, k1, round_lo;
+    float sqrtb;               // the kernels compare in the unnormalised domain: values and thresholds times sqrt(b)
+};
+
+__global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t q = (uint64_t)blockIdx.x * 4u + (threadIdx.x >> 6); // group of four words
+    if (4 * q >= a.W) return;
+    // vertical count: sixteen workers at a time, lane l fetches word (l & 3) of worker (l >> 2) (one coalesced
+    // load), then every fetched word is broadcast and each lane adds its own bit of it
+    int32_t c[4] = { 0, 0, 0, 0 };
+    for (uint32_t m0 = 0; m0 < a.M; m0 += 16u) {
+        const uint32_t m = m0 + (lane >> 2);
+        const uint64_t w = 4 * q + (lane & 3u);
+        const uint64_t mine = (m < a.M && w < a.W) ? a.bits_up[(uint64_t)m * a.W + w] : 0ull;
+        const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
+#pragma unroll
+        for (int i = 0; i < 64; ++i) {
+            const uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine_hi, i) << 32) |
+                                  (uint32_t)__builtin_amdgcn_readlane((int)mine_lo, i);
+            c[i & 3] += __builtin_amdgcn_inverse_ballot_w64(word) ? 1 : 0;
+        }
+    }
+    float val[4], thr[4];
+    uint32_t cnt[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const uint64_t w = 4 * q + s;
+        const uint64_t j = w < a.W ? ((w * 64u + lane) >> a.logb) : 0;
+        val[s] = a.lam[j] * (float)(2 * c[s] - (int32_t)a.M) * (a.sqrtb / (float)a.M);
+        thr[s] = a.lam_s[j] * a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m 2^-24 with m odd
+        cnt[s] = 0u;
+    }
+    for (uint32_t k = 0; k < a.K; ++k) {
+        uint32_t r[4] = { 0u, 0u, 0u, 0u };
+        if (a.dither == 0u) {
+            const RngKey key = { a.k0, a.k1, kDomainDither | (k << 8), a.round_lo, 0xFFFFFFFFu };
+            philox((uint32_t)(q << 6) | lane, key, r);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            float tv = val[s];
+            if (a.dither == 0u) tv = fmaf(thr[s], fmaf((float)(r[s] >> 8), 2.f, -16777215.f), tv);
+            cnt[s] += (tv >= 0.f) ? 1u : 0u;
+        }
+    }
+    for (uint32_t p = 0; p < a.planes; ++p) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const uint64_t word = __ballot(((cnt[s] >> p) & 1u) != 0u);
+            if (lane == (uint32_t)s && 4 * q + s < a.W) a.dst[(uint64_t)p * a.W + 4 * q + s] = word;
+        }
+    }
+}
+
+} // namespace fo

@@ -80,7 +80,7 @@ def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha
         plan.fo_encode(gd[m], rnd, m, bits_up[m], lam_up[m])
     torch.cuda.synchronize()
     h_lam_free = lam_up.cpu().numpy().copy()         # each worker's own amplitude (the rule's value)
-    if eps_mode == 1:
+    if eps_mode >= 1:
         # shared worker eps: everybody quantises with the largest amplitude, per block (what fo_step does)
         lam_up[:] = lam_up.max(dim=0, keepdim=True).values.expand(M, nb)
         for m in range(M):

@@ -48,7 +48,7 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(block_log2=5) == B.EINVAL and create(block_log2=31) == B.EINVAL
     assert create(K=0) == B.EINVAL and create(K=256) == B.EINVAL
     assert create(K=200, d=1 << 25) == B.EINVAL  # K b / 2 would not fit the int32 intermediate
-    assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=2) == B.EINVAL
+    assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=3) == B.EINVAL
     assert create(alpha=1.5) == B.EINVAL and create(alpha_s=float("nan")) == B.EINVAL
     assert create(scale_rule=0, B=0.0) == B.EINVAL
     assert create(d=(1 << 30) + 1) == B.EINVAL

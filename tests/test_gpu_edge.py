@@ -107,6 +107,25 @@ def test_parameter_variants(env, name, kw):
     gates(rep)
 
 
+@pytest.mark.parametrize("name,d,M,blk,K", [
+    ("single_pass", 30_000, 5, 0, 1),
+    ("blocked_small", 7_000, 3, 7, 1),
+    ("blocked", 200_003, 4, 12, 3),
+    ("two_pass", (1 << 18) + 11, 7, 0, 1),
+    ("n2p25", 25_557_032, 3, 0, 1),
+])
+def test_all_shared_eps_zero_transform_server(env, name, d, M, blk, K):
+    """The server shares the workers' eps: its pre-quantisation vector is (lambda / M)(2 c - M) and the kernel
+    applies no transform.  The oracle takes the long way (M decodes, mean, forward transform with the same eps),
+    so this checks the identity H D_eps D_eps H^T = I the shortcut rests on, to the bit."""
+    O, B, inputs, dev = env
+    gs = [inputs.heavy_tailed(d, m) for m in range(M)]
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=blk, seed=0x77 + M, rnd=13, delta=0.02, device=dev,
+                           eps_mode=B.EPS_SHARED_ALL, K=K)
+    print(name, rep, flush=True)
+    gates(rep)
+
+
 def test_forced_scale_is_used(env):
     import torch
     O, B, inputs, dev = env
