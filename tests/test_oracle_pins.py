@@ -355,6 +355,34 @@ def test_average_of_M_dithers_is_K_equals_M_quantizer(oracle):
     assert abs(errs.mean() - want) < 4.5 * errs.std() / math.sqrt(R)
 
 
+def test_all_shared_eps_server_identity_and_unbiasedness(oracle):
+    """Server sharing the workers' eps (a variant outside the paper): (i) its pre-quantisation vector is
+    (lam / M)(2 c - M) exactly, because H D_eps D_eps H^T = I; (ii) the decoded downlink message stays an unbiased
+    estimate of the workers' mean over rounds (the quantiser-moment lemma needs |z| <= lam^s, which holds surely
+    here since |2 c - M| <= M and lam <= lam^s)."""
+    d, M = 64, 3
+    p = oracle.params(d=d, M=M, seed=90, eps_mode=oracle.EPS_SHARED_ALL)
+    gs = [np.random.default_rng(91 + m).standard_normal(d).astype(np.float32) for m in range(M)]
+    lam = np.array([1.3])
+    bits, lams = _uplink(oracle, p, gs, 5, lam=lam)
+    s = oracle.server(p, bits, lams, 5, want_margin=True)
+    c = sum((oracle.unpack(b, d) > 0).astype(np.int64) for b in bits)
+    u = np.asarray(oracle.dither_u(p.seed, 5, 0xFFFFFFFF, 0, np.arange(d))).reshape(d)
+    assert np.allclose(s["margin"], (1.3 / M) * (2 * c - M) + s["lam_s"][0] * u, atol=1e-12)
+    # unbiasedness of the whole round over fresh eps and dithers
+    R = 6000
+    mean = np.zeros(d)
+    want = np.mean([g.astype(np.float64) for g in gs], axis=0)
+    lam_s = None
+    for rnd in range(R):
+        x = np.zeros(d)
+        o = oracle.round_trip(p, gs, x, 1.0, rnd, want=True)
+        mean += o["gd"] / R
+        lam_s = o["lam_s"][0]
+    # every decoded coordinate has second moment (lam^s)^2 (the decoded vector has norm lam^s sqrt(n))
+    assert np.max(np.abs(mean - want)) < 5.0 * lam_s / math.sqrt(R)
+
+
 def test_padding_and_blocking(oracle):
     d = 200
     x = np.random.default_rng(70).standard_normal(d)
