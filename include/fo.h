@@ -165,6 +165,22 @@ int fo_step(fo_plan *plan, const float *const *g, float *x, float delta, uint64_
 int fo_step_messages(fo_plan *plan, const uint64_t **bits_up, const float **scales_up,
                      const uint64_t **bits_down, const float **scales_down);
 
+/* Optional counters (diagnostics; not part of the paper's method, but they watch its hypotheses).  While a stats
+ * block is attached, every encode adds to it; the caller clears it (e.g. hipMemsetAsync) when it wants a fresh
+ * count.  Attached counters cost the encodes a second sweep over their registers; detached (NULL, the default)
+ * they cost nothing.
+ *   clipped  coordinates with |(H_eps g)_i| > lambda: the complement of the event on which the flattening
+ *            lemma (Lemma 3.6) holds and the quantiser is unbiased; 0 is the expected value for alpha >= 2
+ *   near_tie coordinates with |(H_eps g)_i + tau_i| < 1e-6 lambda (first dither): where fp32 and fp64 may
+ *            legitimately disagree on the sign
+ * Index: worker n -> [n]; the server's re-encode -> [FO_MAX_WORKERS]. */
+typedef struct {
+    unsigned long long clipped[FO_MAX_WORKERS + 1];
+    unsigned long long near_tie[FO_MAX_WORKERS + 1];
+} fo_stats;
+/* stats: device pointer (8-byte aligned) or NULL to detach. */
+int fo_set_stats(fo_plan *plan, fo_stats *stats);
+
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method).  After
  * fo_profile_begin every kernel the hot calls enqueue on this plan is bracketed by two HIP events
  * on the caller's stream (the first call creates the events: it allocates, the hot calls still do

@@ -23,7 +23,7 @@ MAX_WORKERS = 64
 
 EXPORTS = ("fo_plan_create", "fo_plan_destroy", "fo_padded_len", "fo_packed_words", "fo_num_scales",
            "fo_block_len", "fo_downlink_planes", "fo_scratch_bytes", "fo_last_hip_error", "fo_encode", "fo_decode",
-           "fo_server_aggregate", "fo_step", "fo_step_messages", "fo_profile_begin", "fo_profile_end")
+           "fo_server_aggregate", "fo_step", "fo_step_messages", "fo_set_stats", "fo_profile_begin", "fo_profile_end")
 
 
 class FoError(RuntimeError):
@@ -71,6 +71,7 @@ def load_library():
         lib.fo_server_aggregate.argtypes = [vp, vp, vp, u64, vp, vp, vp, vp]
         lib.fo_step.argtypes = [vp, C.POINTER(vp), vp, C.c_float, u64, vp]
         lib.fo_step_messages.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
+        lib.fo_set_stats.argtypes = [vp, vp]
         lib.fo_profile_begin.argtypes = [vp]
         lib.fo_profile_end.argtypes = [vp, C.POINTER(KernelTime), C.c_size_t, C.POINTER(C.c_size_t)]
         _lib = lib
@@ -154,6 +155,13 @@ class Plan:
         if rc:
             raise FoError(rc, "fo_step_messages")
         return a.value, b.value, c.value, d.value
+
+    def fo_set_stats(self, stats):
+        """Attach (or, with None, detach) a device block of 2 * (MAX_WORKERS + 1) uint64 counters: first the
+        `clipped` counts per worker and for the server, then the `near_tie` counts (struct fo_stats)."""
+        rc = load_library().fo_set_stats(self._h, _ptr(stats))
+        if rc:
+            raise FoError(rc, "fo_set_stats")
 
     def fo_profile_begin(self):
         rc = load_library().fo_profile_begin(self._h)

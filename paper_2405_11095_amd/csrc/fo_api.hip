@@ -144,6 +144,7 @@ struct fo_plan {
     float *scales_up;    // [M][nblocks]
     uint64_t *bits_down; // [planes][W]
     float *scales_down;  // [nblocks]
+    fo_stats *stats;     // device, optional
     Profiler prof;
 };
 
@@ -167,6 +168,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     fo_plan *pl = new (std::nothrow) fo_plan();
     if (!pl) return FO_ENOMEM;
     pl->p = q;
+    pl->stats = nullptr;
     if (q.block_log2 == 0) {
         uint32_t k = 6;
         while (((uint64_t)1 << k) < q.d) ++k;
@@ -328,20 +330,27 @@ int launch_strided(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const Stride
 }
 
 // The packing kernels are compiled per (dither on/off, transform length below 256).
-template <int IN>
-int launch_pack(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigArgs &c, const PtrTab &tab)
+template <int IN, bool STATS>
+int launch_pack_s(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigArgs &c, const PtrTab &tab)
 {
     const bool dither = c.dither == FO_DITHER_UNIFORM, small = c.S < 8;
     const dim3 block(kThreads);
     if (c.K > 1) { // the K-fold quantiser of the server's message
-        if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true, 0, true>, grid, block, st, c, tab);
-        if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 0, true>, grid, block, st, c, tab);
-        return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, true>, grid, block, st, c, tab);
+        if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true, 0, true, STATS>, grid, block, st, c, tab);
+        if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 0, true, STATS>, grid, block, st, c, tab);
+        return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, true, STATS>, grid, block, st, c, tab);
     }
-    if (dither && c.S == 15) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 15>, grid, block, st, c, tab);
-    if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true>, grid, block, st, c, tab);
-    if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false>, grid, block, st, c, tab);
-    return launch(pl, kid, k_contig<IN, OUT_PACK, false, false>, grid, block, st, c, tab);
+    if (dither && c.S == 15) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 15, false, STATS>, grid, block, st, c, tab);
+    if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true, 0, false, STATS>, grid, block, st, c, tab);
+    if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 0, false, STATS>, grid, block, st, c, tab);
+    return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, false, STATS>, grid, block, st, c, tab);
+}
+// The variants with the diagnostic counters compiled in run only while a stats block is attached.
+template <int IN>
+int launch_pack(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigArgs &c, const PtrTab &tab)
+{
+    if (c.stat_clipped) return launch_pack_s<IN, true>(pl, kid, grid, st, c, tab);
+    return launch_pack_s<IN, false>(pl, kid, grid, st, c, tab);
 }
 
 StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
@@ -373,10 +382,16 @@ ContigArgs contig_base(const fo_plan *pl, const Rng &r)
     return c;
 }
 // Messages of the server carry the K-fold quantiser's counts (Def. 3.2); workers' messages are plain signs.
+// Also points the encode at the party's diagnostic counters when a stats block is attached.
 void set_quantiser(ContigArgs &c, const fo_plan *pl, uint32_t party)
 {
     c.K = party == FO_PARTY_SERVER ? pl->p.K : 1u;
     c.planes = party == FO_PARTY_SERVER ? pl->planes : 1u;
+    if (pl->stats) {
+        const uint32_t at = party == FO_PARTY_SERVER ? FO_MAX_WORKERS : party;
+        c.stat_clipped = pl->stats->clipped + at;
+        c.stat_near = pl->stats->near_tie + at;
+    }
 }
 
 constexpr uint32_t kPartyAllWorkers = 0xFFFFFFFEu;
@@ -549,6 +564,15 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid1, st, e, none));
         return FO_OK;
     }
+    if (pl->npass == 0 && pl->stats) {
+        // diagnostic counters attached: the unfused sequence (its encode has the counting variant)
+        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
+        for (uint32_t m = 0; m < M; ++m)
+            FO_TRY(launch_decode(pl, bits_up + (uint64_t)m * pl->W, scales_up + (uint64_t)m * pl->nblocks, round, m, gbar,
+                                 pl->ntot, m == 0 ? STORE_SET : STORE_ACC, mean_coef, 0.f, nullptr, st));
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
+                             nullptr, 0, st);
+    }
     if (pl->npass == 0) {
         // the transform fits a tile: decode, average and re-encode tile by tile in one kernel
         ServerTileArgs sa;
@@ -692,6 +716,14 @@ extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta
     if (rc) return rc;
     return launch_decode(pl, pl->bits_down, pl->scales_down, round, FO_PARTY_SERVER, x, pl->p.d, STORE_AXPY, pl->rsqrtb,
                          delta, pl->buf_a, st);
+}
+
+extern "C" int fo_set_stats(fo_plan *pl, fo_stats *stats)
+{
+    if (!pl) return FO_EINVAL;
+    if (!aligned(stats, 8)) return FO_EALIGN;
+    pl->stats = stats;
+    return FO_OK;
 }
 
 extern "C" int fo_step_messages(fo_plan *pl, const uint64_t **bits_up, const float **scales_up,

@@ -61,6 +61,8 @@ struct ContigArgs {
     float sqrtb;            // threshold in the unnormalised domain = lambda * sqrt(b)
     float out_coef;         // OUT_F32: value = lambda * out_coef * (H^T q)_i  (1/sqrt(b), times 1/M on the server)
     float delta;            // STORE_AXPY: x -= delta * value
+    unsigned long long *stat_clipped; // OUT_PACK, optional: per slot, += #{i : |z_i| > lambda} (flattening failed there)
+    unsigned long long *stat_near;    // OUT_PACK, optional: per slot, += #{i : |z_i + tau_i| < 1e-6 lambda} (first dither)
 };
 
 // DITHER: uniform dither on (OUT_PACK only).  SMALLB: transform length 64 or 128, where the four
@@ -68,12 +70,13 @@ struct ContigArgs {
 // per-value code is branch free.
 // SC > 0: compiled for exactly SC stages inside the tile (SC = 15: transform length >= 2^15), which
 // makes every stage unconditional; SC = 0 reads the stage count from the arguments.
+// STATS: OUT_PACK also adds to the caller's diagnostic counters (see fo_stats).
 // MULTIK: the K-fold averaged quantiser of Def. 3.2 (the server's message when K > 1).  Coordinate i carries
 // c_i = #{k < K : z_i + tau_{k,i} >= 0} in {0..K}, i.e. q_i = 2 c_i - K = (K / lambda) Q_{lambda,K}(z)_i, stored as
 // `planes` bit planes of W words each (plane p holds bit p of every c_i).  OUT_PACK draws K dithers per
 // coordinate and writes the planes; IN_BITS reads them.  K = 1 is the plain sign message and uses MULTIK = false.
 // The work of one workgroup on tile `tile` of party slot `slot`; lds has kLdsWords words.
-template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK>
+template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK, bool STATS = false>
 __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &tab, const uint32_t tile, const uint32_t slot,
                                             uint32_t *const lds)
 {
@@ -336,6 +339,32 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
     };
 
     // ------------------------------------------------------------------ output
+    if constexpr (OUT == OUT_PACK && STATS) {
+        // Diagnostic counters: a second sweep over the registers, compiled only into the variants that are
+        // launched while a stats block is attached (it would cost the others registers).
+        if (a.stat_clipped) {
+            uint32_t clipped = 0u, near = 0u;
+            const float tscale = a.sqrtb * 5.9604644775390625e-08f;
+#pragma unroll
+            for (int g = 0; g < 16; ++g) {
+                uint32_t w[4] = { 0u, 0u, 0u, 0u };
+                if constexpr (DITHER) philox((uint32_t)(((base + local_of(2 * g)) >> 8) << 6) | lane, key_dit, w);
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int r = 2 * g + (s & 1) + 32 * (s >> 1);
+                    const float l = lam[local_of(r) >> S];
+                    float tv = v[r];
+                    if constexpr (DITHER) tv = fmaf(l * tscale, fmaf((float)(w[s] >> 8), 2.f, -16777215.f), tv);
+                    clipped += (uint32_t)__popcll(__ballot(fabsf(v[r]) > l * a.sqrtb));
+                    near += (uint32_t)__popcll(__ballot(fabsf(tv) < 1e-6f * l * a.sqrtb));
+                }
+            }
+            if (lane == 0u) {
+                atomicAdd(a.stat_clipped + slot, (unsigned long long)clipped);
+                atomicAdd(a.stat_near + slot, (unsigned long long)near);
+            }
+        }
+    }
     if constexpr (OUT == OUT_PACK && MULTIK) {
         uint32_t lo[8], hi[8]; // lane j: word of register j, one pair per bit plane
 #pragma unroll
@@ -461,11 +490,11 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
     }
 }
 
-template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false>
+template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false, bool STATS = false>
 __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
 {
     __shared__ uint32_t lds[kLdsWords];
-    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK>(a, tab, blockIdx.x, blockIdx.y, lds);
+    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK, STATS>(a, tab, blockIdx.x, blockIdx.y, lds);
 }
 
 } // namespace fo

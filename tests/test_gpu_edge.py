@@ -226,3 +226,44 @@ def test_shared_worker_eps_popcount_server(env, name, d, M, blk):
                            eps_mode=B.EPS_SHARED_WORKERS)
     print(name, rep, flush=True)
     gates(rep)
+
+
+def test_diagnostic_counters(env):
+    """fo_stats: coordinates where the flattening failed (|z_i| > lambda, expected none for alpha = 2 on dense
+    inputs, some when lambda is forced small) and near-tie coordinates, against counts made from the oracle's
+    flattened vector."""
+    import torch
+    O, B, inputs, dev = env
+    d, M = 200_000, 2
+    plan = B.Plan(d=d, M=M, seed=21)
+    p = O.params(d=d, M=M, seed=21)
+    stats = torch.zeros(2 * (B.MAX_WORKERS + 1), dtype=torch.int64, device=dev)
+    plan.fo_set_stats(stats)
+    gs = [inputs.gaussian(d, m) for m in range(M)]
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan.fo_step([torch.from_numpy(g).to(dev) for g in gs], x, 0.1, 2)
+    torch.cuda.synchronize()
+    h = stats.cpu().numpy()
+    assert np.all(h[:B.MAX_WORKERS + 1] == 0)                       # nothing clipped: alpha = 2 flattens
+    assert h[B.MAX_WORKERS + 1:].sum() < 50                         # a handful of near ties out of 3 * 2^18
+    # force a small amplitude on worker 1: now a known share of the coordinates exceeds it
+    stats.zero_()
+    lam_free = torch.zeros(1, dtype=torch.float32, device=dev)
+    bits = torch.zeros(plan.W, dtype=torch.int64, device=dev)
+    g1 = torch.from_numpy(gs[1]).to(dev)
+    plan.fo_encode(g1, 2, 1, bits, lam_free)
+    lam_small = lam_free * 0.25
+    stats.zero_()
+    plan.fo_encode(g1, 2, 1, bits, lam_small, flags=B.FORCE_SCALE)
+    torch.cuda.synchronize()
+    h = stats.cpu().numpy()
+    r = O.encode(p, gs[1].astype(np.float64), 2, 1, lam=lam_small.cpu().numpy().astype(np.float64), want_margin=True, want_z=True)
+    lam = float(lam_small[0])
+    want_clipped = int(np.count_nonzero(np.abs(r["z"]) > lam))
+    want_near = int(np.count_nonzero(np.abs(r["margin"]) < 1e-6 * lam))
+    assert want_clipped > 1000
+    assert abs(int(h[1]) - want_clipped) <= 3, (h[1], want_clipped)
+    assert abs(int(h[B.MAX_WORKERS + 1 + 1]) - want_near) <= 3, (h[B.MAX_WORKERS + 2], want_near)
+    assert h[0] == 0 and h[B.MAX_WORKERS] == 0
+    plan.fo_set_stats(None)
+    plan.close()
