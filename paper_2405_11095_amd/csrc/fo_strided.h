@@ -82,6 +82,18 @@ struct SL {
     }
 };
 
+// Load through a base pointer that is the same in every lane (held in scalar registers: the load takes the
+// "scalar base + 32-bit lane offset" addressing form instead of 64-bit vector adds) plus a per-lane byte offset.
+template <typename T>
+__device__ __forceinline__ T ld_uniform(const void *uniform_base, uint32_t byte_off)
+{
+    typedef const __attribute__((address_space(1))) char *gptr;
+    const uint64_t v = reinterpret_cast<uint64_t>(uniform_base);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    const gptr g = (gptr)(((uint64_t)hi << 32) | lo);
+    return *(const __attribute__((address_space(1))) T *)(g + byte_off);
+}
+
 // Access through a wave-uniform base pointer plus a 32-bit per-lane byte offset.
 template <typename T>
 __device__ __forceinline__ T ld_at(const void *uniform_base, uint32_t byte_off)
@@ -397,7 +409,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
         auto request = [&](uint32_t m) {
             const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin;
 #pragma unroll
-            for (int p = 0; p < kSP; ++p) raw[p] = ld_at<uint32_t>(src + g.off(L::pa(p)), ota * 2u);
+            for (int p = 0; p < kSP; ++p) raw[p] = ld_uniform<uint32_t>(src + g.off(L::pa(p)), ota * 2u);
         };
         // finish worker m, whose packed tile is in `raw`; with PREFETCH the registers of `raw` are refilled
         // with worker m + 1 as soon as they have been unpacked
