@@ -229,7 +229,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
         }
     }
 
-    // ------------------------------------------------------------------ round 1: b0,b1,b8..b11
+    // ------------------------------------------------------------------ first register round: b0,b1,b8..b11
     if constexpr (IN != IN_BITS) bfly<T, 0>(v); // the decode side did this stage while unpacking
     bfly<T, 1>(v);
     if (S > 8u) bfly<T, 2>(v);
@@ -253,7 +253,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
         swap_reg5_lane5(v);
     }
 
-    // ------------------------------------------------------------------ round 2: b2..b7
+    // ------------------------------------------------------------------ second register round: b2..b7
     bfly<T, 0>(v);
     bfly<T, 1>(v);
     bfly<T, 2>(v);
@@ -327,7 +327,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
         }
     }
 
-    // ------------------------------------------------------------------ round 3: b12,b13,b14
+    // ------------------------------------------------------------------ third register round: b12,b13,b14
     if (S > 12u) bfly<T, 2>(v);
     if (S > 13u) bfly<T, 3>(v);
     if (S > 14u) bfly<T, 4>(v);
