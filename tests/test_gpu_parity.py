@@ -20,7 +20,11 @@ def env(oracle):
 
 CASES = [
     # name, d, M, block_log2, generator
+    ("one_coordinate", 1, 2, 0, "gaussian"),
+    ("one_word", 64, 3, 0, "gaussian"),
+    ("one_word_plus_one", 65, 2, 0, "gaussian"),
     ("tiny_single_tile", 1000, 2, 0, "gaussian"),
+    ("max_workers", 4096, 64, 0, "gaussian"),
     ("one_tile_exact", 1 << 15, 3, 0, "gaussian"),
     ("c1_two_pass_hb1", 1 << 16, 4, 0, "gaussian"),
     ("ragged_two_pass", 70_001, 3, 0, "gaussian"),
@@ -28,9 +32,14 @@ CASES = [
     ("ragged_hb7", (1 << 21) + 12345, 2, 0, "heavy"),
     ("blocked_b64", 5000, 2, 6, "gaussian"),
     ("blocked_b128", 40_000, 2, 7, "gaussian"),
+    ("blocked_b256", 3000, 2, 8, "gaussian"),
+    ("blocked_b512", 70_000, 2, 9, "gaussian"),
     ("blocked_b1024_ragged", 100_003, 3, 10, "layered"),
+    ("blocked_b2048", 50_000, 2, 11, "heavy"),
     ("blocked_b4096", 1 << 18, 2, 12, "layered"),
+    ("blocked_b8192", 100_000, 2, 13, "gaussian"),
     ("blocked_b16384", (1 << 18) + 77, 2, 14, "layered"),
+    ("blocked_b32768", 100_000, 2, 15, "gaussian"),
     ("blocked_b65536", (1 << 19) + 5, 2, 16, "layered"),
     # the benchmark's geometry (n = 2^25: ten strided stages, the specialised kernels), fewer workers
     ("c3_geometry_n2p25", 25_557_032, 3, 0, "heavy"),
