@@ -235,10 +235,10 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
     // the server pass holds so many registers that one workgroup fills a CU: it takes the whole-tile exchange
     constexpr bool WIDE = (MODE == SM_SERVER);
     constexpr uint32_t kXW = WIDE ? kTile : kXWords;
-    __shared__ uint32_t lds[kXW + kEpsWords + kRedWords];
+    __shared__ uint32_t lds[kXW + (WIDE ? 2u : 1u) * kEpsWords + kRedWords]; // the server pass alternates two eps tables
     uint32_t *const xbuf = lds;
     uint32_t *const epsw = lds + kXW;
-    float *const red = reinterpret_cast<float *>(lds + kXW + kEpsWords);
+    float *const red = reinterpret_cast<float *>(lds + kXW + (WIDE ? 2u : 1u) * kEpsWords);
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t slot = blockIdx.y;
@@ -424,20 +424,23 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             }
             if constexpr (PREFETCH) request(m + 1);
             const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
-            __syncthreads(); // the previous worker's eps words and exchange buffer are no longer read
-            fill_eps<L::T>(epsw, g, key_eps, t);
+            // Two eps tables in turn: worker m's table is written while slow waves may still read worker m-1's,
+            // and it is read after this iteration's barrier, which every wave reaches only when done with m-1.
+            uint32_t *const epsm = epsw + (m & 1u) * kEpsWords;
+            fill_eps<L::T>(epsm, g, key_eps, t);
             stages_a<float, LV>(buf, cb);
             if (need_x) {
+                __syncthreads(); // the previous worker's exchange buffer is no longer read
                 exchange_wide<float, LV>(buf, xbuf, lane, wave);
                 stages_b<float, LV>(buf, cb);
             } else {
-                __syncthreads();
+                __syncthreads(); // publishes the eps table
             }
             // acc += (+-c) * value: the eps sign goes into the (non-negative) coefficient's sign bit
             const uint32_t cbits = __float_as_uint(a.scales[(uint64_t)m * a.scales_stride + gb] * a.out_coef);
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
-                const uint32_t w = epsw[(ut_out >> 5) + (upair_out(p) >> 5)];
+                const uint32_t w = epsm[(ut_out >> 5) + (upair_out(p) >> 5)];
                 acc[2 * p] = fmaf(buf[2 * p], __uint_as_float(((w >> eshift) << 31) | cbits), acc[2 * p]);
                 acc[2 * p + 1] = fmaf(buf[2 * p + 1], __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits), acc[2 * p + 1]);
             }
