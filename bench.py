@@ -110,7 +110,7 @@ def main():
         "k_declow": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
-        "k_server_tile": M * W8 + W8,
+        "k_mean_tile": M * W8 + 4 * n,
         "k_shall": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),

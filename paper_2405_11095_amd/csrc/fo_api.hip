@@ -100,7 +100,7 @@ enum KernelId {
     KID_DEC_HIGH,       // k_strided<DEC_LAST>
     KID_SERVER_HIGH,    // k_strided<SERVER> / k_strided<SHARED>
     KID_COUNT_LOW,      // k_contig<IN_COUNT,*>
-    KID_SERVER_TILE,    // k_server_tile
+    KID_SERVER_TILE,    // k_mean_tile
     KID_SHALL,          // k_shall
     KID_SCALES,         // k_finalize_scales / k_fill_scales / k_server_scales
     KID_COUNT
@@ -108,7 +108,7 @@ enum KernelId {
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_server_tile", "k_shall", "scale kernels",
+    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_tile", "k_shall", "scale kernels",
 };
 
 struct Profiler {
@@ -278,10 +278,9 @@ inline bool args_ok(const ShallArgs &z, int)
 {
     return z.bits_up && z.dst && z.lam && z.lam_s && z.M >= 1 && z.M <= FO_MAX_WORKERS && z.K >= 1 && z.planes >= 1;
 }
-inline bool args_ok(const ServerTileArgs &s, const PtrTab &, int)
+inline bool args_ok(const ServerTileArgs &s, int)
 {
-    return s.enc.src && s.enc.dst && s.enc.scales && s.bits_up && s.scales_up && s.M >= 1 && s.M <= FO_MAX_WORKERS &&
-           s.enc.S >= 6 && s.enc.S <= 15;
+    return s.enc.src && s.bits_up && s.scales_up && s.M >= 1 && s.M <= FO_MAX_WORKERS && s.enc.S >= 6 && s.enc.S <= 15;
 }
 inline bool args_ok(const StridedArgs &s, const PtrTab &tab, int kid)
 {
@@ -564,38 +563,17 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid1, st, e, none));
         return FO_OK;
     }
-    if (pl->npass == 0 && pl->stats) {
-        // diagnostic counters attached: the unfused sequence (its encode has the counting variant)
-        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
-        for (uint32_t m = 0; m < M; ++m)
-            FO_TRY(launch_decode(pl, bits_up + (uint64_t)m * pl->W, scales_up + (uint64_t)m * pl->nblocks, round, m, gbar,
-                                 pl->ntot, m == 0 ? STORE_SET : STORE_ACC, mean_coef, 0.f, nullptr, st));
-        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
-                             nullptr, 0, st);
-    }
     if (pl->npass == 0) {
-        // the transform fits a tile: decode, average and re-encode tile by tile in one kernel
+        // the transform fits a tile: the mean tile by tile in registers, then the ordinary encode
+        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
         ServerTileArgs sa;
         sa.enc = contig_base(pl, r);
-        sa.enc.src = gbar_or_null ? gbar_or_null : pl->buf_b; // the mean passes through this buffer
-        sa.enc.dst = bits_down;
-        sa.enc.scales = scales_down;
-        sa.enc.party0 = FO_PARTY_SERVER; sa.enc.eps_party0 = FO_PARTY_SERVER;
-        set_quantiser(sa.enc, pl, FO_PARTY_SERVER);
+        sa.enc.src = gbar;
         sa.bits_up = bits_up; sa.scales_up = scales_up; sa.M = M;
         sa.coef = 2.f * mean_coef; // the decode side carries half values
-        const bool dither = sa.enc.dither == FO_DITHER_UNIFORM, small = sa.enc.S < 8, multik = sa.enc.K > 1;
-        const dim3 grid((unsigned)pl->ntiles, 1), block(kThreads);
-        if (dither && small) {
-            if (multik) return launch(pl, KID_SERVER_TILE, k_server_tile<true, true, true>, grid, block, st, sa, none);
-            return launch(pl, KID_SERVER_TILE, k_server_tile<true, true, false>, grid, block, st, sa, none);
-        }
-        if (dither) {
-            if (multik) return launch(pl, KID_SERVER_TILE, k_server_tile<true, false, true>, grid, block, st, sa, none);
-            return launch(pl, KID_SERVER_TILE, k_server_tile<true, false, false>, grid, block, st, sa, none);
-        }
-        if (multik) return launch(pl, KID_SERVER_TILE, k_server_tile<false, false, true>, grid, block, st, sa, none);
-        return launch(pl, KID_SERVER_TILE, k_server_tile<false, false, false>, grid, block, st, sa, none);
+        FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile, dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, sa));
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
+                             nullptr, 0, st);
     }
     if (pl->npass == 2) {
         // three-pass transforms: unfused (decode each worker into the mean, then a plain encode)

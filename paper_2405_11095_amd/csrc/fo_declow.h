@@ -37,10 +37,13 @@ constexpr uint32_t walsh_mask32(int j)
 // Decode-side stages of one tile from its 1024 packed 32-bit words, result in layout LC as 32 packed pairs.
 // SC = 15: all fifteen stages (transform length >= 2^15); SC = 0: the S = 6..15 stages of a blocked transform
 // (stage k runs iff k < S; the popcount stages b0..b4 always do).  words points at the party's packed vector.
-// xbuf: kXWords words of LDS.  Ends with the workgroup past a barrier, so xbuf may be reused at once.
+// xa, xb: kXWords words of LDS each for the first (wave-private) and the second (workgroup-wide) exchange; they
+// may be the same buffer.  The second exchange starts with a barrier (all earlier reads of xb are over) and its
+// reads are not followed by one: a caller that loops must not write xb again before its next barrier, which a
+// second call does by itself when xa and xb differ.
 template <int SC>
-__device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xbuf,
-                                            s16x2 (&v)[32])
+__device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xa,
+                                            uint32_t *xb, s16x2 (&v)[32])
 {
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t S = SC ? (uint32_t)SC : S_arg;
@@ -63,7 +66,7 @@ __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, u
 
     // ------------------------------------------------------------------ exchange LA -> LB (inside each half wave)
     {
-        uint32_t *const wb = xbuf + wave * 2112u + (lane >> 5) * 1056u;
+        uint32_t *const wb = xa + wave * 2112u + (lane >> 5) * 1056u;
         const uint32_t col = lane & 31u;
 #pragma unroll
         for (int r = 0; r < 32; ++r) wb[r * 33 + col] = __builtin_bit_cast(uint32_t, v[r]);
@@ -86,16 +89,15 @@ __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, u
         const uint32_t b11 = (lane >> 4) & 1u, b10 = lane >> 5;
         const uint32_t wofs = (lane & 15u) + b10 * 512u + b11 * 1024u + wave * 2048u + 16u * (b11 + 2u * wave);
 #pragma unroll
-        for (int r = 0; r < 32; ++r) xbuf[wofs + r * 16] = __builtin_bit_cast(uint32_t, v[r]);
+        for (int r = 0; r < 32; ++r) xb[wofs + r * 16] = __builtin_bit_cast(uint32_t, v[r]);
     }
     __syncthreads();
     {
         const uint32_t rofs = lane + wave * 256u + 16u * (wave >> 2);
 #pragma unroll
         for (int r = 0; r < 32; ++r) // register r = (b12,b13,b14,b7,b8)
-            v[r] = __builtin_bit_cast(s16x2, xbuf[rofs + ((r >> 3) & 1) * 64 + (r >> 4) * 128 + (r & 7) * (2048 + 32)]);
+            v[r] = __builtin_bit_cast(s16x2, xb[rofs + ((r >> 3) & 1) * 64 + (r >> 4) * 128 + (r & 7) * (2048 + 32)]);
     }
-    __syncthreads(); // the buffer is free again
     if (S > 12u) bfly<s16x2, 0, 32>(v);
     if (S > 13u) bfly<s16x2, 1, 32>(v);
     if (S > 14u) bfly<s16x2, 2, 32>(v);
@@ -120,7 +122,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
     const uint32_t tile = blockIdx.x, slot = blockIdx.y;
     const uint32_t *src = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
     s16x2 v[32];
-    declow_tile<15>(src, a.W, tile, 15u, xbuf, v);
+    declow_tile<15>(src, a.W, tile, 15u, xbuf, xbuf, v);
 
     // store: a wave writes 256 contiguous bytes per register
     uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<int16_t *>(a.dst) + slot * a.dst_stride + ((uint64_t)tile << kTileLog2));

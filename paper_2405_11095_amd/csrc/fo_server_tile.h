@@ -1,33 +1,32 @@
-// Server step for transforms that fit one tile (transform length b <= 2^15, whole or blocked), in one kernel:
-// for every tile, decode the M workers' messages one after the other (Def. 3.8), accumulate
-// gbar = (1/M) sum_n lambda_n D_eps_n H^T q_n (eq. "server average") in registers, and re-encode the tile with
-// (eps^s, lambda^s, K) (Sec. 4, "Server-to-workers encoding").  Per tile the kernel reads M * 4 KiB of packed
-// signs and writes 4 KiB per bit plane; the M decoded vectors never exist in memory.
-//
-// The decode half is declow_tile (popcount + packed int16) with the accumulation done in its output layout; the
-// encode half is the generic tile pipeline, which wants its input in its own load layout, so the mean of the
-// tile makes one trip through global memory inside the kernel (128 KiB that the same workgroup reads straight
-// back: a cache hit; it is also the optional gbar output).
+// Kernels for transforms that fit one tile (transform length b <= 2^15, whole or blocked), built on declow_tile
+// (popcount + packed int16) with the amplitude, the eps flip and the store or accumulation done in its output
+// layout.
+//   k_mean_tile  : the server's mean gbar = (1/M) sum_n lambda_n D_eps_n H^T q_n (Def. 3.8, eq. "server average"):
+//                  per tile, the M messages are decoded one after the other and summed in registers; the M decoded
+//                  vectors never exist in memory (M * 4 KiB of packed signs in, 128 KiB of fp32 out per tile).
+//                  The re-encode of the mean is the ordinary encode kernel.  (A variant that also re-encoded the
+//                  tile in the same kernel was measured slower: it needs so many registers that one 512-thread
+//                  workgroup fills a CU.)
+//   k_decode_tile: one party's decoder with store / accumulate / SGD update.
 #pragma once
 #include "fo_declow.h"
 
 namespace fo {
 
 struct ServerTileArgs {
-    ContigArgs enc;           // the re-encode: src = mean buffer (fp32 [ntot]), dst = downlink planes, scales = lambda^s
+    ContigArgs enc;           // geometry and generator key; src = mean buffer (fp32 [len_in], written here)
     const uint64_t *bits_up;  // [M][W]
     const float *scales_up;   // [M][nblocks]
     uint32_t M;
     float coef;               // value = lambda_n * coef * (half-valued integer): 2 / (sqrt(b) M)
 };
 
-template <bool DITHER, bool SMALLB, bool MULTIK>
-__global__ __launch_bounds__(kThreads, 2) void k_server_tile(const ServerTileArgs sa, const PtrTab tab)
+__global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs sa)
 {
-    __shared__ uint32_t lds[kLdsWords];
+    // two sets of tables used in turn, so that the worker loop needs no barrier of its own
+    __shared__ uint32_t lds[kXWords + 2 * (kEpsWords + kLamWords)];
     uint32_t *const xbuf = lds;
-    uint32_t *const epsw = lds + kXWords;
-    float *const lam = reinterpret_cast<float *>(lds + kXWords + kEpsWords);
+    uint32_t *const tables = lds + kXWords;
     const ContigArgs &a = sa.enc;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x;
@@ -43,8 +42,11 @@ __global__ __launch_bounds__(kThreads, 2) void k_server_tile(const ServerTileArg
     for (int r = 0; r < 64; ++r) acc[r] = 0.f;
 
     for (uint32_t m = 0; m < sa.M; ++m) {
-        // tables of worker m for this tile: 1024 eps words (256 generator calls) and one coefficient per block;
-        // the barriers inside declow_tile publish them, its last one lets the next worker overwrite them
+        // tables of worker m for this tile: 1024 eps words (256 generator calls) and one coefficient per block.
+        // The barriers inside declow_tile publish them; every wave passes those only when it is done with worker
+        // m-1, so the set of worker m-2 may be overwritten without waiting.
+        uint32_t *const epsw = tables + (m & 1u) * (kEpsWords + kLamWords);
+        float *const lam = reinterpret_cast<float *>(epsw + kEpsWords);
         if (t < 256u) {
             const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
             uint32_t w[4];
@@ -57,16 +59,20 @@ __global__ __launch_bounds__(kThreads, 2) void k_server_tile(const ServerTileArg
             lam[t] = gb < a.nblocks ? sa.scales_up[(uint64_t)m * a.nblocks + gb] * sa.coef : 0.f;
         }
         s16x2 v[32];
-        declow_tile<0>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, v);
+        declow_tile<0>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, xbuf, v);
+        __syncthreads(); // the exchange buffer is read; the next worker's first exchange may write it
+        // the table addresses are recomputed for every worker: hoisted out of the loop they would hold 64 registers
+        // next to the 64 accumulators
+        uint32_t dtl = dt;
+        asm volatile("" : "+v"(dtl));
 #pragma unroll
         for (int r = 0; r < 32; ++r) {
-            const uint32_t D = dt + declow_reg_dword(r);
+            const uint32_t D = dtl + declow_reg_dword(r);
             const uint32_t w = epsw[D >> 4];
             const uint32_t cbits = __float_as_uint(lam[D >> (S - 1u)]); // non-negative: the eps sign goes into bit 31
             acc[2 * r] = fmaf((float)v[r].x, __uint_as_float(((w >> eshift) << 31) | cbits), acc[2 * r]);
             acc[2 * r + 1] = fmaf((float)v[r].y, __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits), acc[2 * r + 1]);
         }
-        __syncthreads(); // tables read; the next worker may refill them
     }
 
     // the mean of the tile, natural order
@@ -79,9 +85,6 @@ __global__ __launch_bounds__(kThreads, 2) void k_server_tile(const ServerTileArg
             if (D < room) gq[D] = make_float2(acc[2 * r], acc[2 * r + 1]);
         }
     }
-    __syncthreads(); // workgroup-scope release / acquire: the tile is read back below by other waves
-
-    contig_tile<IN_GRAD, OUT_PACK, DITHER, SMALLB, 0, MULTIK>(a, tab, tile, 0u, lds);
 }
 
 // Decoder of one party for transforms that fit a tile (Def. 3.8): out = lambda D_eps H^T q, first len_out
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
     }
     s16x2 v[32];
     const uint32_t *words = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
-    declow_tile<0>(words, a.W, tile, S, xbuf, v); // its barriers publish the tables
+    declow_tile<0>(words, a.W, tile, S, xbuf, xbuf, v); // its barriers publish the tables
 
     float2 *dst = reinterpret_cast<float2 *>(static_cast<float *>(a.dst) + base);
     const uint64_t room = a.len_out > base ? a.len_out - base : 0; // valid coordinates of this tile
