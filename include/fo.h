@@ -173,7 +173,8 @@ int fo_step_messages(fo_plan *plan, const uint64_t **bits_up, const float **scal
  *            lemma (Lemma 3.6) holds and the quantiser is unbiased; 0 is the expected value for alpha >= 2
  *   near_tie coordinates with |(H_eps g)_i + tau_i| < 1e-6 lambda (first dither): where fp32 and fp64 may
  *            legitimately disagree on the sign
- * Index: worker n -> [n]; the server's re-encode -> [FO_MAX_WORKERS]. */
+ * Index: worker n -> [n]; the server's re-encode -> [FO_MAX_WORKERS] (the zero-transform server of
+ * FO_EPS_SHARED_ALL adds nothing: its vector is bounded by lambda <= lambda^s by construction). */
 typedef struct {
     unsigned long long clipped[FO_MAX_WORKERS + 1];
     unsigned long long near_tie[FO_MAX_WORKERS + 1];

@@ -26,6 +26,9 @@ def env(oracle):
     ("eight_planes_K255", 70_000, 2, 0, 255, {}),
     ("no_dither_K3", 40_000, 2, 0, 3, dict(dither=1)),
     ("three_pass_K3", (1 << 25) + 5, 1, 0, 3, {}),
+    ("shared_eps_two_pass_K2", 90_000, 3, 0, 2, dict(eps_mode=1)),
+    ("shared_eps_single_pass_K6", 9_000, 3, 0, 6, dict(eps_mode=1)),
+    ("all_shared_two_pass_K4", 90_000, 3, 0, 4, dict(eps_mode=2)),
 ])
 def test_round_trip_with_averaged_downlink(env, name, d, M, blk, K, kw):
     O, B, inputs, dev = env
