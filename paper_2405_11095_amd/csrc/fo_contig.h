@@ -225,7 +225,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
         for (int c = 0; c < 16; ++c) {
             const uint32_t nib = epsw[wave * 128u + c * 8u + (lane >> 3)] >> ((lane & 7u) * 4u);
 #pragma unroll
-            for (int k = 0; k < 4; ++k) v[4 * c + k] = flip_if(v[4 * c + k], (nib >> k) & 1u);
+            for (int k = 0; k < 4; ++k) v[4 * c + k] = flip_by_bit31(v[4 * c + k], nib << (31 - k));
         }
     }
 

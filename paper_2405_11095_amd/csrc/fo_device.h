@@ -74,6 +74,11 @@ __device__ __forceinline__ float flip_if(float x, uint32_t bit) // bit in {0,1}
 {
     return __uint_as_float(__float_as_uint(x) ^ (bit << 31));
 }
+// x with its sign flipped when bit 31 of w is set: x ^ (w & 0x80000000) as one three-input operation
+__device__ __forceinline__ float flip_by_bit31(float x, uint32_t w)
+{
+    return __uint_as_float(__builtin_amdgcn_bitop3_b32(__float_as_uint(x), w, 0x80000000u, 0x78));
+}
 
 template <typename T, int BIT, int V = kV>
 __device__ __forceinline__ void bfly(T (&v)[V])
