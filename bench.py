@@ -76,11 +76,20 @@ def main():
     print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "
           f"plan scratch {plan.scratch_bytes / 2**30:.2f} GiB", file=sys.stderr, flush=True)
 
+    copy_gbs = None
     if args.copy_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9   # read + write of 1 GiB, five times
+        print(f"[bench] 1 GiB device-to-device copy: {copy_gbs:.0f} GB/s (read + write)", file=sys.stderr, flush=True)
         del src, dst
 
     delta = 1e-3
@@ -128,6 +137,8 @@ def main():
         "step_model_bytes": sum(v for k, v in per_step.items() if k in per_kernel),
     }
     roofline["step_frac_of_hbm_peak"] = round(roofline["step_model_bytes"] / sec / 1e9 / HBM_PEAK_GBS, 4)
+    if copy_gbs:
+        roofline["device_copy_gbs"] = round(copy_gbs, 1)   # what a plain copy of 1 GiB reaches on this machine
 
     cpu = None
     if not args.no_cpu_baseline:
