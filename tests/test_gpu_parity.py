@@ -59,3 +59,17 @@ def test_round_trip_parity(env, name, d, M, blk, kind):
     rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=blk, seed=0xF05D + len(name), rnd=7, delta=0.05, device=dev)
     print(rep, flush=True)
     gates(rep)
+
+
+def test_c3_at_full_size_in_the_benchmark_configuration(env):
+    """The benchmark's workload as bench.py runs it (d = 25,557,032, n = 2^25, M = 16, batched launches through
+    fo_step): every uplink bit of all 16 workers, the mean, every downlink bit, the decoded vector and the updated
+    iterate against the oracle; fo_step's messages equal the ones of the calls made by hand."""
+    O, B, inputs, dev = env
+    wl = inputs.WORKLOADS["c3"]
+    gs = inputs.workload("c3")
+    rep = check_round_trip(O, B, gs, d=wl["d"], M=wl["M"], block_log2=0, seed=0xF05D + 3, rnd=2, delta=1e-3, device=dev,
+                           threads=16)
+    print(rep, flush=True)
+    gates(rep)
+    assert rep["uplink_exempt"] < 5000 and rep["downlink_exempt"] < 500   # near ties: about one coordinate in a million
