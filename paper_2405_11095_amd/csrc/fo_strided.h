@@ -94,6 +94,18 @@ __device__ __forceinline__ T ld_uniform(const void *uniform_base, uint32_t byte_
     return *(const __attribute__((address_space(1))) T *)(g + byte_off);
 }
 
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
+template <typename T>
+__device__ __forceinline__ void st_uniform(void *uniform_base, uint32_t byte_off, T value)
+{
+    typedef __attribute__((address_space(1))) char *gptr;
+    const uint64_t v = reinterpret_cast<uint64_t>(uniform_base);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    const gptr g = (gptr)(((uint64_t)hi << 32) | lo);
+    *(__attribute__((address_space(1))) T *)(g + byte_off) = value;
+}
+
 // Access through a wave-uniform base pointer plus a 32-bit per-lane byte offset.
 template <typename T>
 __device__ __forceinline__ T ld_at(const void *uniform_base, uint32_t byte_off)
@@ -300,8 +312,12 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
                 const uint32_t ro = g.off(L::pa(p)); // wave-uniform
                 const uint64_t e = (uint64_t)ro + ota;
                 float2 d = make_float2(0.f, 0.f);
-                if (e + 1 < room) d = ld_at<float2>(src + ro, ota * 4u);
-                else if (e < room) d.x = ld_at<float>(src + ro, ota * 4u);
+                if (e + 1 < room) {
+                    const f32x2 q = ld_uniform<f32x2>(src + ro, ota * 4u);
+                    d = make_float2(q.x, q.y);
+                } else if (e < room) {
+                    d.x = ld_uniform<float>(src + ro, ota * 4u);
+                }
                 v[2 * p] = d.x;
                 v[2 * p + 1] = d.y;
             }
@@ -370,11 +386,11 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             TV *dst = static_cast<TV *>(a.dst) + slot * a.dst_stride + g.origin;
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
-                using T2 = typename std::conditional<FIN, float2, int2>::type;
+                using T2 = typename std::conditional<FIN, f32x2, i32x2>::type;
                 T2 d;
                 d.x = v[2 * p];
                 d.y = v[2 * p + 1];
-                ref_at<T2>(dst + g.off(upair_out(p)), ot_out * 4u) = d;
+                st_uniform<T2>(dst + g.off(upair_out(p)), ot_out * 4u, d);
             }
         }
     } else {
