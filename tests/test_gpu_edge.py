@@ -267,3 +267,19 @@ def test_diagnostic_counters(env):
     assert h[0] == 0 and h[B.MAX_WORKERS] == 0
     plan.fo_set_stats(None)
     plan.close()
+    # the counting variants of the K-fold server encode and of the single-tile path: same messages as without counters
+    for dd, blk, K in ((70_000, 0, 3), (20_000, 9, 1), (20_000, 0, 2)):
+        gs2 = [torch.from_numpy(inputs.gaussian(dd, m)).to(dev) for m in range(M)]
+        got = []
+        for attach in (False, True):
+            pl = B.Plan(d=dd, M=M, block_log2=blk, K=K, seed=33)
+            if attach:
+                stats.zero_()
+                pl.fo_set_stats(stats)
+            xx = torch.zeros(dd, dtype=torch.float32, device=dev)
+            pl.fo_step(gs2, xx, 0.1, 4)
+            torch.cuda.synchronize()
+            got.append(xx.clone())
+            pl.close()
+        assert torch.equal(got[0], got[1])
+        assert int(stats[:B.MAX_WORKERS + 1].sum()) == 0
