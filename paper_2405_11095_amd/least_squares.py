@@ -37,7 +37,8 @@ class LeastSquares:
         scale = float(self.d) ** -0.5
         out = self.buf[:len(idx)]
         for k, i in enumerate(idx):
-            self.gen.manual_seed(self.seed * 4_294_967_296 + int(i))
+            # the CPU generator keeps only the low 32 bits of a seed: mix seed and row index into them
+            self.gen.manual_seed(((self.seed * 1_000_003 + int(i)) * 2_654_435_761 + 12_345) % (1 << 63))
             out[k].normal_(0.0, scale, generator=self.gen)
         return out
 
