@@ -283,3 +283,31 @@ def test_diagnostic_counters(env):
             pl.close()
         assert torch.equal(got[0], got[1])
         assert int(stats[:B.MAX_WORKERS + 1].sum()) == 0
+
+
+def test_caller_streams_and_two_plans(env):
+    """All work goes to the caller's stream: two plans driven from two (default-priority) streams at the same time
+    give what each gives alone on the default stream."""
+    import torch
+    O, B, inputs, dev = env
+    d, M = 300_000, 3
+    gs = [torch.from_numpy(inputs.gaussian(d, m)).to(dev) for m in range(M)]
+
+    def run(plan, stream, rounds):
+        x = torch.zeros(d, dtype=torch.float32, device=dev)
+        with torch.cuda.stream(stream):
+            for r in range(rounds):
+                plan.fo_step(gs, x, 0.01, r)
+        return x
+
+    p0 = B.Plan(d=d, M=M, seed=3)
+    ref = run(p0, torch.cuda.default_stream(), 6)
+    torch.cuda.synchronize()
+    p1, p2 = B.Plan(d=d, M=M, seed=3), B.Plan(d=d, M=M, seed=3)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    x1 = run(p1, s1, 6)
+    x2 = run(p2, s2, 6)
+    torch.cuda.synchronize()
+    assert torch.equal(x1, ref) and torch.equal(x2, ref)
+    for p in (p0, p1, p2):
+        p.close()
