@@ -33,7 +33,12 @@
  * Scales.  A party's scales[j] is the dither amplitude lambda_j of block j in the paper's
  * (orthonormal) normalisation: lambda = alpha * B * sqrt(ln b / b) (Thm 5.5), with B the caller's
  * bound (FO_SCALE_BOUND) or the block's measured l2 norm (FO_SCALE_L2).  The server amplitude is
- * lambda^s_j = alpha_s * max_n lambda_{n,j} * sqrt(ln b) (Thm 5.5).
+ * lambda^s_j = alpha_s * max_n lambda_{n,j} * sqrt(ln b) (Thm 5.5).  That rule bounds the mean by
+ * ||gbar|| <= lambda sqrt(b); the server lemma in the proof only needs
+ * lambda^s >= alpha_s sqrt(ln b / b) ||gbar||, and FO_SERVER_SCALE_L2 takes exactly that, with the norm of
+ * the mean the server has just formed.  It is between sqrt(M) (when the uplink's quantisation noise dominates
+ * gbar, the usual case) and alpha sqrt(ln b) times smaller, which cuts the downlink's error term by that
+ * factor squared.  Not available with FO_EPS_SHARED_ALL.
  *
  * Shared worker eps (FO_EPS_SHARED_WORKERS, a variant the paper does not have).  When every worker
  * uses the same eps_t and the same amplitude, linearity of H^T turns the server's M decodes into one:
@@ -87,6 +92,9 @@ extern "C" {
 #define FO_EPS_SHARED_WORKERS 1u /* one eps for all workers, an independent one for the server */
 #define FO_EPS_SHARED_ALL 2u /* one eps for the workers and the server (flagged variant, see above) */
 
+#define FO_SERVER_SCALE_THM 0u /* lambda^s = alpha_s max_n lambda_n sqrt(ln b)  (Thm 5.5 as stated)            */
+#define FO_SERVER_SCALE_L2 1u  /* lambda^s = alpha_s sqrt(ln b / b) ||gbar_block||_2 (measured, see "Scales")  */
+
 #define FO_PARTY_SERVER 0xFFFFFFFFu /* party id of the server; workers are 0 .. M-1      */
 #define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */
 
@@ -105,6 +113,7 @@ typedef struct {
     float alpha_s;       /* server amplitude factor, >= 2                                 */
     float B;             /* norm bound for FO_SCALE_BOUND, > 0 (ignored by FO_SCALE_L2)   */
     uint64_t seed;
+    uint32_t server_scale; /* FO_SERVER_SCALE_*; 0 = the theorem's rule                        */
 } fo_params;
 
 typedef struct fo_plan fo_plan;

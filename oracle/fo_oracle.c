@@ -40,6 +40,8 @@
 #define ORC_EPS_INDEPENDENT 0u
 #define ORC_EPS_SHARED_WORKERS 1u
 #define ORC_EPS_SHARED_ALL 2u
+#define ORC_SERVER_SCALE_THM 0u
+#define ORC_SERVER_SCALE_L2 1u
 
 typedef struct {
     uint64_t d;          /* logical gradient length                                  */
@@ -51,6 +53,7 @@ typedef struct {
     uint32_t eps_mode;   /* ORC_EPS_*                                                */
     double alpha, alpha_s, B;
     uint64_t seed;
+    uint32_t server_scale; /* ORC_SERVER_SCALE_*                                        */
 } orc_params;
 
 /* ------------------------------------------------------------------------------------------ */
@@ -359,7 +362,19 @@ void orc_server(const orc_params *p, const uint64_t *bits_up, const double *lam_
     for (uint64_t i = 0; i < ntot; ++i) gbar[i] /= (double)p->M;
     free(q);
     free(dec);
-    if (!force_s) orc_server_lambda(p, lam_up, lam_s);
+    if (!force_s) {
+        if (p->server_scale == ORC_SERVER_SCALE_L2) {
+            /* The smallest amplitude the server lemma in the proof of Thm 5.5 admits: it only uses
+             * lambda^s >= alpha_s sqrt(log n / n) ||w|| for the vector w being encoded, here gbar (per block). */
+            for (uint64_t j = 0; j < nb; ++j) {
+                double s2 = 0.0;
+                for (uint64_t l = 0; l < b; ++l) s2 += gbar[j * b + l] * gbar[j * b + l];
+                lam_s[j] = orc_lambda(p->alpha_s, sqrt(s2), b);
+            }
+        } else {
+            orc_server_lambda(p, lam_up, lam_s);
+        }
+    }
     /* the server encodes a vector of length ntot: same geometry, logical length ntot */
     orc_params ps = *p;
     ps.d = ntot;

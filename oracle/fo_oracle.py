@@ -21,6 +21,7 @@ PARTY_SERVER = 0xFFFFFFFF
 DITHER_UNIFORM, DITHER_NONE = 0, 1
 SCALE_BOUND, SCALE_L2 = 0, 1
 EPS_INDEPENDENT, EPS_SHARED_WORKERS, EPS_SHARED_ALL = 0, 1, 2
+SERVER_SCALE_THM, SERVER_SCALE_L2 = 0, 1
 DOMAIN_EPS, DOMAIN_DITHER = 1, 2
 
 
@@ -37,13 +38,13 @@ class Params(C.Structure):
     _fields_ = [("d", C.c_uint64), ("M", C.c_uint32), ("block_log2", C.c_uint32),
                 ("K", C.c_uint32), ("dither", C.c_uint32), ("scale_rule", C.c_uint32),
                 ("eps_mode", C.c_uint32), ("alpha", C.c_double), ("alpha_s", C.c_double),
-                ("B", C.c_double), ("seed", C.c_uint64)]
+                ("B", C.c_double), ("seed", C.c_uint64), ("server_scale", C.c_uint32)]
 
 
 def params(d, M=1, block_log2=0, K=1, dither=DITHER_UNIFORM, scale_rule=SCALE_L2,
-           eps_mode=EPS_INDEPENDENT, alpha=2.0, alpha_s=2.0, B=1.0, seed=0) -> Params:
+           eps_mode=EPS_INDEPENDENT, alpha=2.0, alpha_s=2.0, B=1.0, seed=0, server_scale=SERVER_SCALE_THM) -> Params:
     return Params(int(d), int(M), int(block_log2), int(K), int(dither), int(scale_rule),
-                  int(eps_mode), float(alpha), float(alpha_s), float(B), int(seed))
+                  int(eps_mode), float(alpha), float(alpha_s), float(B), int(seed), int(server_scale))
 
 
 _lib = None

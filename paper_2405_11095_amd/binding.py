@@ -17,6 +17,7 @@ OK, EINVAL, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4
 DITHER_UNIFORM, DITHER_NONE = 0, 1
 SCALE_BOUND, SCALE_L2 = 0, 1
 EPS_INDEPENDENT, EPS_SHARED_WORKERS, EPS_SHARED_ALL = 0, 1, 2
+SERVER_SCALE_THM, SERVER_SCALE_L2 = 0, 1
 PARTY_SERVER = 0xFFFFFFFF
 FORCE_SCALE = 1
 MAX_WORKERS = 64
@@ -39,7 +40,8 @@ class FoError(RuntimeError):
 class Params(C.Structure):
     _fields_ = [("d", C.c_uint64), ("M", C.c_uint32), ("block_log2", C.c_uint32), ("K", C.c_uint32),
                 ("dither", C.c_uint32), ("scale_rule", C.c_uint32), ("eps_mode", C.c_uint32),
-                ("alpha", C.c_float), ("alpha_s", C.c_float), ("B", C.c_float), ("seed", C.c_uint64)]
+                ("alpha", C.c_float), ("alpha_s", C.c_float), ("B", C.c_float), ("seed", C.c_uint64),
+                ("server_scale", C.c_uint32)]
 
 
 class KernelTime(C.Structure):
@@ -98,10 +100,10 @@ class Plan:
     """Owner of an fo_plan.  Methods mirror the C entry points one to one."""
 
     def __init__(self, d, M=1, block_log2=0, K=1, dither=DITHER_UNIFORM, scale_rule=SCALE_L2,
-                 eps_mode=EPS_INDEPENDENT, alpha=2.0, alpha_s=2.0, B=1.0, seed=0):
+                 eps_mode=EPS_INDEPENDENT, alpha=2.0, alpha_s=2.0, B=1.0, seed=0, server_scale=SERVER_SCALE_THM):
         lib = load_library()
         self.params = Params(int(d), int(M), int(block_log2), int(K), int(dither), int(scale_rule),
-                             int(eps_mode), float(alpha), float(alpha_s), float(B), int(seed))
+                             int(eps_mode), float(alpha), float(alpha_s), float(B), int(seed), int(server_scale))
         h = C.c_void_p()
         rc = lib.fo_plan_create(C.byref(self.params), C.byref(h))
         if rc:

@@ -133,6 +133,7 @@ struct fo_plan {
     uint32_t hb[2];      // stages of each strided pass (pass 0 is adjacent to the contiguous tile)
     uint32_t planes;     // bit planes of the downlink message: ceil(log2(K + 1))
     float coef_lambda, sqrtb, rsqrtb, coef_s;
+    float coef_lambda_s; // alpha_s sqrt(ln b / b): measured-norm rule for the server
     // scratch (device)
     char *scratch;
     size_t scratch_bytes;
@@ -164,6 +165,8 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
         return FO_EINVAL;
     if (!(q.alpha >= 2.f) || !(q.alpha_s >= 2.f)) return FO_EINVAL;
     if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
+    if (q.server_scale != FO_SERVER_SCALE_THM && q.server_scale != FO_SERVER_SCALE_L2) return FO_EINVAL;
+    if (q.server_scale == FO_SERVER_SCALE_L2 && q.eps_mode == FO_EPS_SHARED_ALL) return FO_EINVAL;
 
     fo_plan *pl = new (std::nothrow) fo_plan();
     if (!pl) return FO_ENOMEM;
@@ -199,6 +202,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     pl->sqrtb = (float)std::sqrt(bd);
     pl->rsqrtb = (float)(1.0 / std::sqrt(bd));
     pl->coef_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd)));
+    pl->coef_lambda_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd) / bd));
 
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t sz_a = pl->npass ? up((size_t)q.M * pl->ntot * 4) : 0;
@@ -421,6 +425,9 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     c.scales = scales; c.scales_stride = scales_stride;
     c.party0 = party0; c.eps_party0 = eps_party_of(pl, party0);
     set_quantiser(c, pl, party0);
+    // amplitude from a measured norm: alpha for a worker, alpha_s for the server's own vector
+    const float coef = party0 == FO_PARTY_SERVER ? pl->coef_lambda_s : pl->coef_lambda;
+    c.coef_lambda = coef;
     const dim3 cgrid((unsigned)((pl->nblocks + 255) / 256));
     if (pl->npass == 0) {
         c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
@@ -452,7 +459,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     }
     if (!scales_given) {
         FO_TRY(launch(pl, KID_SCALES, k_finalize_scales, dim3((unsigned)pl->nblocks, nslots), dim3(256), st, pl->partials,
-                           pl->ntiles, (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda, scales, scales_stride));
+                           pl->ntiles, (uint32_t)(pl->b >> kTileLog2), coef, scales, scales_stride));
         if (common) FO_TRY(launch(pl, KID_SCALES, k_common_scales, cgrid, dim3(256), st, scales, pl->nblocks, nslots));
     }
     c.src = tmp; c.src_stride = tmp_stride;
@@ -516,8 +523,15 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
     const uint32_t M = pl->p.M;
     PtrTab none;
     std::memset(&none, 0, sizeof(none));
-    FO_TRY(launch(pl, KID_SCALES, k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), st, scales_up,
-                       pl->nblocks, M, pl->coef_s, scales_down));
+    // server amplitude: the theorem's rule from the workers' amplitudes now, or from the norm of the mean later
+    const bool l2s = pl->p.server_scale == FO_SERVER_SCALE_L2;
+    if (!l2s)
+        FO_TRY(launch(pl, KID_SCALES, k_server_scales, dim3((unsigned)((pl->nblocks + 255) / 256)), dim3(256), st, scales_up,
+                           pl->nblocks, M, pl->coef_s, scales_down));
+    auto finalize_server_scales = [&]() -> int { // after a fused strided pass that left the tile sums of squares of gbar
+        return launch(pl, KID_SCALES, k_finalize_scales, dim3((unsigned)pl->nblocks, 1), dim3(256), st, pl->partials, pl->ntiles,
+                      (uint32_t)(pl->b >> kTileLog2), pl->coef_lambda_s, scales_down, (uint64_t)0);
+    };
     const float mean_coef = pl->rsqrtb / (float)M;
     const bool zero_transform = pl->p.eps_mode == FO_EPS_SHARED_ALL;
     if (zero_transform) {
@@ -543,7 +557,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
             c.dst = gbar; c.len_out = pl->ntot; c.store_mode = STORE_SET; c.out_coef = mean_coef;
             FO_TRY(launch(pl, KID_COUNT_LOW, (k_contig<IN_COUNT, OUT_F32>), grid1, block, st, c, none));
             if (zero_transform) return FO_OK;
-            return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down,
+            return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down,
                                  0, nullptr, 0, st);
         }
         c.dst = pl->buf_a; c.dst_stride = 0;
@@ -553,8 +567,10 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.scales = scales_up; s.scales_stride = 0;
         s.gbar = gbar_or_null;
         s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
+        s.partials = l2s ? pl->partials : nullptr;
         FO_TRY(launch_strided<SM_SHARED>(pl, KID_SERVER_HIGH, grid1, st, s, none));
         if (zero_transform) return FO_OK;
+        if (l2s) FO_TRY(finalize_server_scales());
         ContigArgs e = contig_base(pl, r);
         e.src = pl->buf_b; e.dst = bits_down;
         e.scales = scales_down;
@@ -572,7 +588,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         sa.bits_up = bits_up; sa.scales_up = scales_up; sa.M = M;
         sa.coef = 2.f * mean_coef; // the decode side carries half values
         FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile, dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, sa));
-        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
                              nullptr, 0, st);
     }
     if (pl->npass == 2) {
@@ -583,7 +599,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
                                    pl->ntot, m == 0 ? STORE_SET : STORE_ACC, mean_coef, 0.f, pl->buf_a, st);
             if (rc) return rc;
         }
-        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, true, bits_down, 0, scales_down, 0,
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
                              pl->buf_a, 0, st);
     }
     // two-pass transforms: M low-stage passes (bits -> int32), one fused high-stage pass that forms the mean
@@ -601,7 +617,9 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.scales = scales_up; s.scales_stride = pl->nblocks;
         s.gbar = gbar_or_null;
         s.M = M; s.out_coef = 2.f * mean_coef; s.eps_party0 = FO_PARTY_SERVER; // int16 input holds half values
+        s.partials = l2s ? pl->partials : nullptr;
         FO_TRY((launch_strided<SM_SERVER, true>(pl, KID_SERVER_HIGH, dim3((unsigned)pl->ntiles, 1), st, s, none)));
+        if (l2s) FO_TRY(finalize_server_scales());
     }
     {
         ContigArgs c = contig_base(pl, r);

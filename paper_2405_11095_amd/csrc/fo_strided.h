@@ -476,6 +476,22 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             for (int p = 0; p < kSP; ++p)
                 ref_at<float2>(gq + g.off(upair_out(p)), ot_out * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
         }
+        // measured-norm server amplitude: this tile's sum of squares of the mean (the eps flip does not change it)
+        if (a.partials) {
+            float ss = 0.f;
+#pragma unroll
+            for (int r = 0; r < kSV; r += 4)
+                ss += (acc[r] * acc[r] + acc[r + 1] * acc[r + 1]) + (acc[r + 2] * acc[r + 2] + acc[r + 3] * acc[r + 3]);
+            ss = wave_sum(ss, 6);
+            __syncthreads(); // red is free
+            if (lane == 0) red[wave] = ss;
+            __syncthreads();
+            if (t == 0) {
+                float tot = 0.f;
+                for (int w = 0; w < L::T / 64; ++w) tot += red[w];
+                a.partials[tile] = tot;
+            }
+        }
         // re-encode: eps^s flip, then the same stages in reverse layout order
         const RngKey key_s = { a.k0, a.k1, kDomainEps, a.round_lo, a.eps_party0 };
         __syncthreads();

@@ -59,15 +59,16 @@ def compare_codes(q_gpu, q_oracle, margin, lam, b):
 
 
 def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha=2.0, alpha_s=2.0,
-                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True, eps_mode=0, x0=None, K=1):
+                     scale_rule=1, dither=0, Bnorm=1.0, threads=8, check_step=True, eps_mode=0, x0=None, K=1,
+                     server_scale=0):
     """Runs encode x M, server, decode and fo_step on the GPU and compares every stage with the
     oracle.  Returns a report dict; asserts nothing (callers apply the gates)."""
     import torch
 
     plan = B.Plan(d=d, M=M, block_log2=block_log2, K=K, dither=dither, scale_rule=scale_rule, alpha=alpha,
-                  alpha_s=alpha_s, B=Bnorm, seed=seed, eps_mode=eps_mode)
+                  alpha_s=alpha_s, B=Bnorm, seed=seed, eps_mode=eps_mode, server_scale=server_scale)
     p = O.params(d=d, M=M, block_log2=block_log2, K=K, dither=dither, scale_rule=scale_rule, alpha=alpha,
-                 alpha_s=alpha_s, B=Bnorm, seed=seed, eps_mode=eps_mode)
+                 alpha_s=alpha_s, B=Bnorm, seed=seed, eps_mode=eps_mode, server_scale=server_scale)
     b, nb, nt = O.geometry(p)
     assert (plan.b, plan.nblocks, plan.ntot) == (b, nb, nt)
     W = nt // 64
@@ -119,7 +120,10 @@ def check_round_trip(O, B, gs, d, M, block_log2, seed, rnd, delta, device, alpha
     rep["lam_rel_err"] = max(r[3] for r in res)
 
     # ---- stage (ii): server, oracle fed the GPU's uplink messages and the GPU's lambda^s
-    free_s = O.server_lambda(p, h_lam_up.astype(np.float64))
+    if server_scale == 0:
+        free_s = O.server_lambda(p, h_lam_up.astype(np.float64))
+    else:   # measured-norm rule: the oracle's own amplitude comes with its own mean
+        free_s = O.server(p, h_bits_up, h_lam_up.astype(np.float64), rnd)["lam_s"]
     den = np.where(free_s > 0, free_s, 1.0)
     rep["lam_s_rel_err"] = float(np.max(np.abs(h_lam_s - free_s) / den))
     s = O.server(p, h_bits_up, h_lam_up.astype(np.float64), rnd, lam_s=h_lam_s.astype(np.float64), want_margin=True)

@@ -37,7 +37,8 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     from paper_2405_11095_amd import binding as B
 
     def create(**kw):
-        base = dict(d=1000, M=2, block_log2=0, K=1, dither=0, scale_rule=1, eps_mode=0, alpha=2.0, alpha_s=2.0, B=1.0, seed=1)
+        base = dict(d=1000, M=2, block_log2=0, K=1, dither=0, scale_rule=1, eps_mode=0, alpha=2.0, alpha_s=2.0, B=1.0, seed=1,
+                    server_scale=0)
         base.update(kw)
         p = B.Params(*[base[k] for k, _ in B.Params._fields_])
         h = C.c_void_p()
@@ -51,6 +52,7 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=3) == B.EINVAL
     assert create(alpha=1.5) == B.EINVAL and create(alpha_s=float("nan")) == B.EINVAL
     assert create(scale_rule=0, B=0.0) == B.EINVAL
+    assert create(server_scale=2) == B.EINVAL and create(server_scale=1, eps_mode=2) == B.EINVAL
     assert create(d=(1 << 30) + 1) == B.EINVAL
     assert create(d=(1 << 26), eps_mode=1) == B.EINVAL          # shared eps is built up to n = 2^25
     assert lib.fo_plan_create(None, None) == B.EINVAL

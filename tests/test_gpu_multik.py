@@ -88,3 +88,58 @@ def test_second_moment_falls_as_one_over_K(env):
         got = float(np.mean(errs))
         assert abs(got - want) <= 0.02 * want, (K, got, want)
         plan.close()
+
+
+@pytest.mark.parametrize("name,d,M,blk,kw", [
+    ("single_pass", 20_000, 3, 0, {}),
+    ("blocked_small", 6_000, 2, 7, {}),
+    ("blocked_4096", 300_000, 3, 12, {}),
+    ("two_pass", 100_000, 4, 0, {}),
+    ("two_pass_K3", 100_000, 3, 0, dict(K=3)),
+    ("blocked_65536", (1 << 18) + 9, 2, 16, {}),
+    ("shared_eps_two_pass", 90_000, 3, 0, dict(eps_mode=1)),
+    ("shared_eps_single_pass", 9_000, 3, 0, dict(eps_mode=1)),
+    ("three_pass", (1 << 25) + 5, 1, 0, {}),
+    ("n2p25", 25_557_032, 2, 0, {}),
+])
+def test_measured_norm_server_amplitude(env, name, d, M, blk, kw):
+    """FO_SERVER_SCALE_L2: lambda^s = alpha_s sqrt(ln b / b) ||gbar_block|| from the mean the server has just formed."""
+    O, B, inputs, dev = env
+    gs = [inputs.heavy_tailed(d, m) for m in range(M)]
+    rep = P.check_round_trip(O, B, gs, d, M, blk, seed=0xABC + M, rnd=5, delta=1e-3, device=dev, server_scale=1, **kw)
+    print(name, rep)
+    P.gates(rep)
+
+
+def test_measured_norm_rule_shrinks_the_downlink_error(env):
+    """Same uplink messages, two server rules.  E||decode - gbar||^2 = (lambda^s)^2 n - ||gbar||^2 (K = 1).  The mean
+    of M independently quantised vectors has ||gbar||^2 of about lambda^2 n / M (quantisation noise dominates), so
+    the theorem's rule, which allows for ||gbar|| = lambda sqrt(n), is about M times the measured-norm rule."""
+    import torch
+    O, B, inputs, dev = env
+    d, M = 1 << 16, 4
+    gs = [torch.from_numpy(inputs.gaussian(d, m)).to(dev) for m in range(M)]
+    err, lam_s_of = {}, {}
+    for rule in (0, 1):
+        plan = B.Plan(d=d, M=M, seed=5, server_scale=rule)
+        bits = torch.zeros((M, plan.W), dtype=torch.int64, device=dev)
+        lam = torch.zeros((M, 1), dtype=torch.float32, device=dev)
+        for m in range(M):
+            plan.fo_encode(gs[m], 1, m, bits[m], lam[m])
+        down = torch.zeros((plan.planes, plan.W), dtype=torch.int64, device=dev)
+        lam_s = torch.zeros(1, dtype=torch.float32, device=dev)
+        gbar = torch.zeros(plan.ntot, dtype=torch.float32, device=dev)
+        out = torch.zeros(d, dtype=torch.float32, device=dev)
+        plan.fo_server_aggregate(bits, lam, 1, down, lam_s, gbar)
+        plan.fo_decode(down, lam_s, 1, SERVER, out)
+        torch.cuda.synchronize()
+        nb2 = float((gbar.double() ** 2).sum())
+        err[rule] = float(((out - gbar[:d]).double() ** 2).sum())
+        lam_s_of[rule] = float(lam_s[0])
+        # the identity above holds exactly for every draw: the decoded vector has norm lambda^s sqrt(n) and the
+        # cross term <decode, gbar> has mean ||gbar||^2; check it loosely on this one draw
+        want = lam_s_of[rule] ** 2 * d - nb2
+        assert abs(err[rule] - want) < 0.1 * want, (rule, err[rule], want)
+        plan.close()
+    ratio = err[0] / err[1]
+    assert 0.6 * M < ratio < 1.6 * M, (err, lam_s_of, ratio)

@@ -383,6 +383,36 @@ def test_all_shared_eps_server_identity_and_unbiasedness(oracle):
     assert np.max(np.abs(mean - want)) < 5.0 * lam_s / math.sqrt(R)
 
 
+def test_measured_norm_server_amplitude(oracle):
+    """Server rule L2: lambda^s = alpha_s sqrt(ln n / n) ||gbar||, per block; it is the smallest amplitude the
+    server lemma of Thm 5.5 admits, never larger than the theorem's rule (||gbar|| <= lambda sqrt(n)), and the
+    flattening event ||H_eps^s gbar||_inf <= lambda^s it is chosen for fails with probability <= 2 n^(-alpha_s^2/4)
+    over eps^s (Lemma 3.6), here <= 2/n per round."""
+    d, M, blk = 600, 3, 8                       # three blocks of 256, the last one padded
+    p = oracle.params(d=d, M=M, block_log2=blk, seed=70, server_scale=oracle.SERVER_SCALE_L2)
+    pt = oracle.params(d=d, M=M, block_log2=blk, seed=70)
+    gs = [np.random.default_rng(80 + m).standard_normal(d).astype(np.float32) for m in range(M)]
+    b, nb, nt = oracle.geometry(p)
+    bits, lams = _uplink(oracle, p, gs, 4)
+    s, st = oracle.server(p, bits, lams, 4, want_margin=True), oracle.server(pt, bits, lams, 4)
+    assert np.array_equal(s["gbar"], st["gbar"])
+    norms = np.linalg.norm(s["gbar"].reshape(nb, b), axis=1)
+    assert np.allclose(s["lam_s"], 2.0 * math.sqrt(math.log(b) / b) * norms, rtol=1e-13)
+    assert np.all(s["lam_s"] <= st["lam_s"])
+    # the downlink message is the (eps^s, lambda^s)-encoding of gbar with that amplitude
+    us = oracle.dither_u(p.seed, 4, SERVER, 0, np.arange(nt))
+    r = oracle.encode(oracle.params(d=nt, M=M, block_log2=blk, seed=70), s["gbar"], 4, SERVER, lam=s["lam_s"], want_margin=True, want_z=True)
+    assert np.allclose(s["margin"], r["z"] + np.repeat(s["lam_s"], b) * us, atol=1e-12)
+    # flattening event over rounds (fresh eps^s each round)
+    fails, R = 0, 400
+    for rnd in range(R):
+        bits, lams = _uplink(oracle, p, gs, rnd)
+        sr = oracle.server(p, bits, lams, rnd)
+        z = oracle.encode(oracle.params(d=nt, M=M, block_log2=blk, seed=70), sr["gbar"], rnd, SERVER, lam=sr["lam_s"], want_z=True)["z"]
+        fails += int(np.count_nonzero(np.abs(z) > np.repeat(sr["lam_s"], b)))
+    assert fails <= 50                      # Lemma 3.6 allows up to 2 R nb = 2400 in expectation; observed: 1
+
+
 def test_padding_and_blocking(oracle):
     d = 200
     x = np.random.default_rng(70).standard_normal(d)
