@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--block-log2", type=int, default=None,
                     help="transform length 2^k (default: the workload's first entry; c4 has 10, 12, 14, 16)")
     ap.add_argument("--K", type=int, default=1, help="averaging count of the downlink quantiser")
+    ap.add_argument("--server-scale", default="thm", choices=["thm", "l2"],
+                    help="server amplitude: Thm 5.5 as stated (default) or from the measured norm of the mean")
     ap.add_argument("--eps-mode", default="independent", choices=["independent", "shared", "all"],
                     help="independent: the paper's protocol (default, the headline number); shared: one eps for all "
                          "workers and the popcount server; all: the server shares that eps too and needs no transform")
@@ -71,7 +73,8 @@ def main():
     eps_mode = {"independent": B.EPS_INDEPENDENT, "shared": B.EPS_SHARED_WORKERS, "all": B.EPS_SHARED_ALL}[args.eps_mode]
     blk = wl["block_log2"][0] if args.block_log2 is None else args.block_log2
     seed = 0xF05D + int(args.workload[1])
-    plan = B.Plan(d=d, M=M, block_log2=blk, K=args.K, seed=seed, eps_mode=eps_mode)
+    srv = B.SERVER_SCALE_L2 if args.server_scale == "l2" else B.SERVER_SCALE_THM
+    plan = B.Plan(d=d, M=M, block_log2=blk, K=args.K, seed=seed, eps_mode=eps_mode, server_scale=srv)
     n = plan.ntot
     print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "
           f"plan scratch {plan.scratch_bytes / 2**30:.2f} GiB", file=sys.stderr, flush=True)
@@ -145,7 +148,7 @@ def main():
         from oracle import fo_oracle as O
         Ms = min(8, M)                                   # bounded sample: the first Ms workers, full d
         nthreads = max(1, min(Ms, 16, os.cpu_count() or 1))
-        p = O.params(d=d, M=Ms, block_log2=blk, K=args.K, seed=seed, eps_mode=int(eps_mode))
+        p = O.params(d=d, M=Ms, block_log2=blk, K=args.K, seed=seed, eps_mode=int(eps_mode), server_scale=int(srv))
         xo = np.zeros(d, dtype=np.float64)
         c0 = time.perf_counter()
         O.round_trip(p, gs_host[:Ms], xo, delta, 0, nthreads=nthreads)
@@ -162,7 +165,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: d={d} fp32 padded to n={n}, M={M} workers, "
                                f"{'full-length' if blk == 0 else f'blocks of 2^{blk}'} randomized FWHT, uniform dither, "
-                               f"L2 scale rule, alpha=alpha_s=2, K={args.K}, {args.eps_mode} eps, one fo_step per step",
+                               f"L2 scale rule, alpha=alpha_s=2, K={args.K}, {args.eps_mode} eps, server amplitude {args.server_scale}, "
+                               f"one fo_step per step",
                    "d": d, "n": n, "M": M, "block_log2": blk},
         "roofline": roofline, "cpu_baseline": cpu,
     }
