@@ -311,3 +311,32 @@ def test_caller_streams_and_two_plans(env):
     assert torch.equal(x1, ref) and torch.equal(x2, ref)
     for p in (p0, p1, p2):
         p.close()
+
+
+def test_per_kernel_timing(env):
+    """fo_profile_begin / fo_profile_end: every kernel of the step is reported with its launch count and a positive
+    time; the times add up to no more than the wall time of the steps."""
+    import time
+    import torch
+    O, B, inputs, dev = env
+    d, M = 1 << 18, 4
+    gs = [torch.from_numpy(inputs.gaussian(d, m)).to(dev) for m in range(M)]
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan = B.Plan(d=d, M=M, seed=8)
+    plan.fo_step(gs, x, 0.01, 0)
+    torch.cuda.synchronize()
+    plan.fo_profile_begin()
+    t0 = time.perf_counter()
+    for r in range(5):
+        plan.fo_step(gs, x, 0.01, r + 1)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    prof = plan.fo_profile_end()
+    assert {"k_strided<ENC_FIRST>", "k_contig<IN_F32,OUT_PACK>", "k_declow", "k_strided<SERVER>", "k_strided<DEC_LAST>",
+            "scale kernels"} <= set(prof)
+    assert prof["k_strided<ENC_FIRST>"][0] == 5 and prof["k_contig<IN_F32,OUT_PACK>"][0] == 10
+    assert all(ms > 0 for _, ms in prof.values())
+    assert sum(ms for _, ms in prof.values()) <= wall_ms
+    with pytest.raises(B.FoError):
+        plan.fo_profile_end()          # not recording any more
+    plan.close()
