@@ -59,7 +59,7 @@ __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, u
             const uint32_t both = (uint32_t)__builtin_popcount(w ^ walsh_mask32(2 * k)) + (hi << 16);
             v[x * 16 + k] = __builtin_bit_cast(s16x2, both);
             // blocked transforms take the popcount's offset off here; the full-tile case does it at the end
-            if constexpr (SC == 0) v[x * 16 + k] -= (s16x2)(16, 16);
+            if constexpr (SC == 0) v[x * 16 + k] -= s16x2{ 16, 16 };
         }
     }
     if (S > 11u) bfly<s16x2, 4, 32>(v); // b11
@@ -104,7 +104,7 @@ __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, u
 
     // the popcount offset, gathered by the ten later stages on the coordinates with b5..b14 = 0
     if constexpr (SC == 15)
-        if (t < 16u) v[0] -= (s16x2)(16384, 16384);
+        if (t < 16u) v[0] -= s16x2{ 16384, 16384 };
 }
 
 // dword index (= coordinate / 2) inside the tile of register r of this thread in layout LC
