@@ -168,6 +168,15 @@ int fo_server_aggregate(fo_plan *plan, const uint64_t *bits_up, const float *sca
 int fo_step(fo_plan *plan, const float *const *g, float *x, float delta, uint64_t round,
             void *hip_stream);
 
+/* fo_step with the iteration counter read on the device when the kernels run: round_dev is a device uint64 (8-byte
+ * aligned).  For callers that capture the step into a HIP graph (problem sizes where the step is a chain of short
+ * launches): the graph is captured once and replayed, the caller advancing *round_dev between replays (for example
+ * with an increment kernel captured into the same graph).  eps and dither depend on the round, so replaying a
+ * step captured with a fixed round would reuse them; this entry point exists to avoid that.  The library records
+ * no memset and nothing but kernel launches on the stream. */
+int fo_step_dev_round(fo_plan *plan, const float *const *g, float *x, float delta, const uint64_t *round_dev,
+                      void *hip_stream);
+
 /* Device pointers into plan scratch holding the messages of the last fo_step on this plan:
  * bits_up [M][W], scales_up [M][nblocks], bits_down [P][W], scales_down [nblocks].  Any out
  * argument may be NULL.  Valid until the next hot call on the plan. */
@@ -202,6 +211,10 @@ typedef struct {
     float total_ms;    /* sum of the launches' durations                                         */
 } fo_kernel_time;
 int fo_profile_begin(fo_plan *plan);
+/* The same, bracketing only the launches of the named kernel (a name fo_profile_end reports): two event records
+ * per launch of one kernel instead of all, for timing that kernel inside a region whose total time also counts
+ * (events between kernels keep one from starting while the previous one drains: about 3 % on a 2 ms step). */
+int fo_profile_begin_kernel(fo_plan *plan, const char *kernel_name);
 int fo_profile_end(fo_plan *plan, fo_kernel_time *out, size_t cap, size_t *count);
 
 #ifdef __cplusplus

@@ -24,7 +24,7 @@ MAX_WORKERS = 64
 
 EXPORTS = ("fo_plan_create", "fo_plan_destroy", "fo_padded_len", "fo_packed_words", "fo_num_scales",
            "fo_block_len", "fo_downlink_planes", "fo_scratch_bytes", "fo_last_hip_error", "fo_encode", "fo_decode",
-           "fo_server_aggregate", "fo_step", "fo_step_messages", "fo_set_stats", "fo_profile_begin", "fo_profile_end")
+           "fo_server_aggregate", "fo_step", "fo_step_dev_round", "fo_step_messages", "fo_set_stats", "fo_profile_begin", "fo_profile_begin_kernel", "fo_profile_end")
 
 
 class FoError(RuntimeError):
@@ -72,9 +72,11 @@ def load_library():
         lib.fo_decode.argtypes = [vp, vp, vp, u64, u32, vp, vp]
         lib.fo_server_aggregate.argtypes = [vp, vp, vp, u64, vp, vp, vp, vp]
         lib.fo_step.argtypes = [vp, C.POINTER(vp), vp, C.c_float, u64, vp]
+        lib.fo_step_dev_round.argtypes = [vp, C.POINTER(vp), vp, C.c_float, vp, vp]
         lib.fo_step_messages.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp)]
         lib.fo_set_stats.argtypes = [vp, vp]
         lib.fo_profile_begin.argtypes = [vp]
+        lib.fo_profile_begin_kernel.argtypes = [vp, C.c_char_p]
         lib.fo_profile_end.argtypes = [vp, C.POINTER(KernelTime), C.c_size_t, C.POINTER(C.c_size_t)]
         _lib = lib
     return _lib
@@ -150,6 +152,13 @@ class Plan:
         if rc:
             raise FoError(rc, "fo_step")
 
+    def fo_step_dev_round(self, g_list, x, delta, round_dev, stream=None):
+        """fo_step with the round read from a device uint64 (a one-element int64 tensor) at kernel run time."""
+        arr = (C.c_void_p * self.M)(*[_ptr(g) for g in g_list])
+        rc = load_library().fo_step_dev_round(self._h, arr, _ptr(x), delta, _ptr(round_dev), _stream(stream))
+        if rc:
+            raise FoError(rc, "fo_step_dev_round")
+
     def fo_step_messages(self):
         """Device addresses (ints) of the last fo_step's messages inside plan scratch."""
         a, b, c, d = C.c_void_p(), C.c_void_p(), C.c_void_p(), C.c_void_p()
@@ -169,6 +178,11 @@ class Plan:
         rc = load_library().fo_profile_begin(self._h)
         if rc:
             raise FoError(rc, "fo_profile_begin")
+
+    def fo_profile_begin_kernel(self, name):
+        rc = load_library().fo_profile_begin_kernel(self._h, name.encode())
+        if rc:
+            raise FoError(rc, "fo_profile_begin_kernel")
 
     def fo_profile_end(self):
         """{kernel name: (launches, total_ms)} for the kernels that ran since fo_profile_begin."""

@@ -117,6 +117,7 @@ struct Profiler {
     hipEvent_t *ev = nullptr; // 2 * kMax events
     int kid[kMax];
     int used = 0;
+    int only = -1; // >= 0: bracket launches of this kernel only
 };
 
 } // namespace
@@ -146,6 +147,7 @@ struct fo_plan {
     uint64_t *bits_down; // [planes][W]
     float *scales_down;  // [nblocks]
     fo_stats *stats;     // device, optional
+    const unsigned long long *round_dev; // device, set for the duration of fo_step_dev_round
     Profiler prof;
 };
 
@@ -172,6 +174,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     if (!pl) return FO_ENOMEM;
     pl->p = q;
     pl->stats = nullptr;
+    pl->round_dev = nullptr;
     if (q.block_log2 == 0) {
         uint32_t k = 6;
         while (((uint64_t)1 << k) < q.d) ++k;
@@ -258,10 +261,13 @@ namespace {
 
 struct Rng {
     uint32_t k0, k1, round_lo;
+    const unsigned long long *round_dev;
 };
 Rng rng_of(const fo_plan *pl, uint64_t round)
 {
-    return { (uint32_t)pl->p.seed, (uint32_t)(pl->p.seed >> 32) ^ (uint32_t)(round >> 32), (uint32_t)round };
+    // with a device-side round counter the kernels finish the key themselves (resolve_round)
+    if (pl->round_dev) return { (uint32_t)pl->p.seed, (uint32_t)(pl->p.seed >> 32), 0u, pl->round_dev };
+    return { (uint32_t)pl->p.seed, (uint32_t)(pl->p.seed >> 32) ^ (uint32_t)(round >> 32), (uint32_t)round, nullptr };
 }
 
 // Host-side guard against launching a kernel with a pointer it will dereference left unset.
@@ -306,7 +312,7 @@ int launch(fo_plan *pl, int kid, Kern kernel, dim3 grid, dim3 block, hipStream_t
         return FO_EHIP;
     }
     Profiler &pf = pl->prof;
-    const bool rec = pf.on && pf.used < Profiler::kMax;
+    const bool rec = pf.on && (pf.only < 0 || pf.only == kid) && pf.used < Profiler::kMax;
     if (rec && !hip_ok(hipEventRecord(pf.ev[2 * pf.used], st), "hipEventRecord")) return FO_EHIP;
     hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
     if (!hip_ok(hipGetLastError(), kKernelNames[kid])) return FO_EHIP;
@@ -363,7 +369,7 @@ StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
     s.hb = pl->hb[pass];
     s.ls = pass == 0 ? (uint32_t)kTileLog2 : (uint32_t)kTileLog2 + pl->hb[0];
     s.logb = pl->logb;
-    s.k0 = r.k0; s.k1 = r.k1; s.round_lo = r.round_lo;
+    s.k0 = r.k0; s.k1 = r.k1; s.round_lo = r.round_lo; s.round_dev = r.round_dev;
     s.len_in = s.len_out = pl->ntot;
     return s;
 }
@@ -377,7 +383,7 @@ ContigArgs contig_base(const fo_plan *pl, const Rng &r)
     c.S = pl->S;
     c.logb = pl->logb;
     c.dither = pl->p.dither;
-    c.k0 = r.k0; c.k1 = r.k1; c.round_lo = r.round_lo;
+    c.k0 = r.k0; c.k1 = r.k1; c.round_lo = r.round_lo; c.round_dev = r.round_dev;
     c.coef_lambda = pl->coef_lambda;
     c.sqrtb = pl->sqrtb;
     c.len_in = c.len_out = pl->ntot;
@@ -539,7 +545,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         ShallArgs z;
         z.bits_up = bits_up; z.dst = bits_down; z.lam = scales_up; z.lam_s = scales_down;
         z.W = pl->W; z.logb = pl->logb; z.M = M; z.K = pl->p.K; z.planes = pl->planes; z.dither = pl->p.dither;
-        z.k0 = r.k0; z.k1 = r.k1; z.round_lo = r.round_lo; z.sqrtb = pl->sqrtb;
+        z.k0 = r.k0; z.k1 = r.k1; z.round_lo = r.round_lo; z.round_dev = r.round_dev; z.sqrtb = pl->sqrtb;
         FO_TRY(launch(pl, KID_SHALL, k_shall, dim3((unsigned)((pl->W + 15) / 16)), dim3(256), st, z));
         if (!gbar_or_null) return FO_OK;
         // the mean itself was asked for (checking): one inverse transform of the summed sign vectors, below
@@ -714,6 +720,17 @@ extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta
                          delta, pl->buf_a, st);
 }
 
+extern "C" int fo_step_dev_round(fo_plan *pl, const float *const *g, float *x, float delta, const uint64_t *round_dev,
+                                 void *hip_stream)
+{
+    if (!pl || !round_dev) return FO_EINVAL;
+    if (!aligned(round_dev, 8)) return FO_EALIGN;
+    pl->round_dev = reinterpret_cast<const unsigned long long *>(round_dev);
+    const int rc = fo_step(pl, g, x, delta, 0, hip_stream);
+    pl->round_dev = nullptr;
+    return rc;
+}
+
 extern "C" int fo_set_stats(fo_plan *pl, fo_stats *stats)
 {
     if (!pl) return FO_EINVAL;
@@ -744,7 +761,21 @@ extern "C" int fo_profile_begin(fo_plan *pl)
             if (!hip_ok(hipEventCreate(&pf.ev[i]), "hipEventCreate")) return FO_EHIP;
     }
     pf.used = 0;
+    pf.only = -1;
     pf.on = true;
+    return FO_OK;
+}
+
+extern "C" int fo_profile_begin_kernel(fo_plan *pl, const char *kernel_name)
+{
+    if (!pl || !kernel_name) return FO_EINVAL;
+    int kid = -1;
+    for (int k = 0; k < KID_COUNT; ++k)
+        if (std::strcmp(kKernelNames[k], kernel_name) == 0) kid = k;
+    if (kid < 0) return FO_EINVAL;
+    const int rc = fo_profile_begin(pl);
+    if (rc) return rc;
+    pl->prof.only = kid;
     return FO_OK;
 }
 

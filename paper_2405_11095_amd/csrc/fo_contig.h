@@ -57,6 +57,7 @@ struct ContigArgs {
     uint32_t party0;        // party id of slot 0 (slot y is party0 + y); FO_PARTY_SERVER stays as is
     uint32_t eps_party0;    // same for the eps stream
     uint32_t k0, k1, round_lo;
+    const unsigned long long *round_dev; // optional: round counter read at run time (see resolve_round)
     float coef_lambda;      // alpha * sqrt(ln b / b)
     float sqrtb;            // threshold in the unnormalised domain = lambda * sqrt(b)
     float out_coef;         // OUT_F32: value = lambda * out_coef * (H^T q)_i  (1/sqrt(b), times 1/M on the server)
@@ -91,8 +92,10 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
     const uint32_t S = SC ? (uint32_t)SC : a.S;
     const uint32_t party = (a.party0 == 0xFFFFFFFFu) ? a.party0 : a.party0 + slot;
     const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
-    const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
-    const RngKey key_dit = { a.k0, a.k1, kDomainDither, a.round_lo, party };
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
+    const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, eps_party };
+    const RngKey key_dit = { a.k0, rk1, kDomainDither, rlo, party };
 
     T v[kV];
 

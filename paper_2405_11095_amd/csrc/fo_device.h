@@ -58,6 +58,21 @@ __device__ __forceinline__ void philox(uint32_t counter, const RngKey &key, uint
     out[0] = x0; out[1] = x1; out[2] = x2; out[3] = x3;
 }
 
+// The round counter enters the generator key (low word as counter word 2, high word xored into key word 1).
+// It is either fixed at launch (dev == nullptr: k1_in already holds the xor) or read from device memory when
+// the kernel runs, so that a captured graph can be replayed for one round after the other.
+__device__ __forceinline__ void resolve_round(uint32_t k1_in, uint32_t lo_in, const unsigned long long *dev, uint32_t &k1,
+                                              uint32_t &lo)
+{
+    k1 = k1_in;
+    lo = lo_in;
+    if (dev) {
+        const unsigned long long r = *dev;
+        lo = (uint32_t)r;
+        k1 = k1_in ^ (uint32_t)(r >> 32);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Small helpers
 // ---------------------------------------------------------------------------------------------

@@ -31,6 +31,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x;
     const uint32_t S = a.S;
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
     const uint64_t base = (uint64_t)tile << kTileLog2;
     const uint32_t nblk_tile = kTile >> S;
     const uint64_t blk0 = (uint64_t)tile * nblk_tile;
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
         uint32_t *const epsw = tables + (m & 1u) * (kEpsWords + kLamWords);
         float *const lam = reinterpret_cast<float *>(epsw + kEpsWords);
         if (t < 256u) {
-            const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
+            const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, m };
             uint32_t w[4];
             philox((uint32_t)(base >> 7) + t, key_eps, w);
 #pragma unroll
@@ -100,6 +102,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x, slot = blockIdx.y;
     const uint32_t S = a.S;
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
     const uint64_t base = (uint64_t)tile << kTileLog2;
     const uint32_t nblk_tile = kTile >> S;
     const uint32_t dt = lane | (wave << 8);
@@ -107,7 +111,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
     const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
 
     if (t < 256u) {
-        const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
+        const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, eps_party };
         uint32_t w[4];
         philox((uint32_t)(base >> 7) + t, key_eps, w);
 #pragma unroll

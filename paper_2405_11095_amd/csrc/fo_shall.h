@@ -17,6 +17,7 @@ struct ShallArgs {
     uint64_t W;
     uint32_t logb, M, K, planes, dither;
     uint32_t k0, k1, round_lo;
+    const unsigned long long *round_dev; // optional: round counter read at run time
     float sqrtb;               // the kernels compare in the unnormalised domain: values and thresholds times sqrt(b)
 };
 
@@ -25,6 +26,8 @@ __global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t q = (uint64_t)blockIdx.x * 4u + (threadIdx.x >> 6); // group of four words
     if (4 * q >= a.W) return;
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
     // vertical count: sixteen workers at a time, lane l fetches word (l & 3) of worker (l >> 2) (one coalesced
     // load), then every fetched word is broadcast and each lane adds its own bit of it
     int32_t c[4] = { 0, 0, 0, 0 };
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
     for (uint32_t k = 0; k < a.K; ++k) {
         uint32_t r[4] = { 0u, 0u, 0u, 0u };
         if (a.dither == 0u) {
-            const RngKey key = { a.k0, a.k1, kDomainDither | (k << 8), a.round_lo, 0xFFFFFFFFu };
+            const RngKey key = { a.k0, rk1, kDomainDither | (k << 8), rlo, 0xFFFFFFFFu };
             philox((uint32_t)(q << 6) | lane, key, r);
         }
 #pragma unroll

@@ -44,6 +44,7 @@ struct StridedArgs {
     uint32_t store_mode;
     uint32_t eps_party0;
     uint32_t k0, k1, round_lo;
+    const unsigned long long *round_dev; // optional: round counter read at run time
     float out_coef;        // value = lambda * out_coef * (transformed integer)
     float delta;
 };
@@ -254,6 +255,8 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t slot = blockIdx.y;
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
     const uint32_t hb = HB ? (uint32_t)HB : a.hb;
     const uint32_t cb = (uint32_t)kTileLog2 - hb;
     // 64-byte row segments (int16 input, 32 columns): neighbouring column groups share 128-byte lines, so
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
     if constexpr (MODE != SM_SERVER && MODE != SM_SHARED) {
         TV v[kSV];
         const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
-        const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, eps_party };
+        const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, eps_party };
         if constexpr (MODE == SM_ENC_FIRST || MODE == SM_DEC_LAST) fill_eps<L::T>(epsw, g, key_eps, t);
 
         // ---------------------------------------------------------------- load (LA)
@@ -400,7 +403,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             // one tile: remaining inverse stages of H^T (sum of the workers' sign vectors), amplitude / M, shared eps
             static_assert(!IN16, "the summed sign vectors need an int32 intermediate");
             int32_t v[kSV];
-            const RngKey key_w = { a.k0, a.k1, kDomainEps, a.round_lo, 0xFFFFFFFEu };
+            const RngKey key_w = { a.k0, rk1, kDomainEps, rlo, 0xFFFFFFFEu };
             fill_eps<L::T>(epsw, g, key_w, t);
             load_int(v, static_cast<const char *>(a.src) + g.origin * 4u);
             stages_a<int32_t, LV>(v, cb);
@@ -439,7 +442,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
                 buf[2 * p + 1] = (float)((int32_t)raw[p] >> 16);
             }
             if constexpr (PREFETCH) request(m + 1);
-            const RngKey key_eps = { a.k0, a.k1, kDomainEps, a.round_lo, m };
+            const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, m };
             // Two eps tables in turn: worker m's table is written while slow waves may still read worker m-1's,
             // and it is read after this iteration's barrier, which every wave reaches only when done with m-1.
             uint32_t *const epsm = epsw + (m & 1u) * kEpsWords;
@@ -493,7 +496,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             }
         }
         // re-encode: eps^s flip, then the same stages in reverse layout order
-        const RngKey key_s = { a.k0, a.k1, kDomainEps, a.round_lo, a.eps_party0 };
+        const RngKey key_s = { a.k0, rk1, kDomainEps, rlo, a.eps_party0 };
         __syncthreads();
         fill_eps<L::T>(epsw, g, key_s, t);
         __syncthreads();
