@@ -62,3 +62,14 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert lib.fo_server_aggregate(None, None, None, 0, None, None, None, None) == B.EINVAL
     assert lib.fo_step(None, None, None, 0.0, 0, None) == B.EINVAL
     assert lib.fo_padded_len(None) == 0
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    """No CPU fallback: without the built HIP library the binding refuses to work."""
+    from paper_2405_11095_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "libfo.so"))
+    with pytest.raises(FileNotFoundError):
+        binding.load_library()
+    with pytest.raises(FileNotFoundError):
+        binding.Plan(d=100)
