@@ -25,11 +25,11 @@ HBM_PEAK_GBS = 8000.0
 # by 1.000, the factors of a 1 GiB copy; profiles/c3_fo_step_hbm_traffic.md), keyed by kernel name.  For the
 # kernels launched with two batch sizes per step the figure is the per-step sum divided by two.
 MEASURED_TRAFFIC = {
-    "k_strided<ENC_FIRST>": 3783790505,
-    "k_contig<IN_F32,OUT_PACK>": (2214774329 + 138659606) // 2,
-    "k_strided<SERVER>": 1208282163,
-    "k_declow": (1140952572 + 71407452) // 2,
-    "k_strided<DEC_LAST>": 271913847,
+    "k_strided<ENC_FIRST>": 3783807574,
+    "k_contig<IN_F32,OUT_PACK>": (2214798093 + 138661273) // 2,
+    "k_strided<SERVER>": 1208240742,
+    "k_declow": (1140953485 + 71407510) // 2,
+    "k_strided<DEC_LAST>": 271920344,
 }
 
 
