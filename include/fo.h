@@ -38,7 +38,7 @@
  * lambda^s >= alpha_s sqrt(ln b / b) ||gbar||, and FO_SERVER_SCALE_L2 takes exactly that, with the norm of
  * the mean the server has just formed.  It is between sqrt(M) (when the uplink's quantisation noise dominates
  * gbar, the usual case) and alpha sqrt(ln b) times smaller, which cuts the downlink's error term by that
- * factor squared.  Not available with FO_EPS_SHARED_ALL.
+ * factor squared.
  *
  * Shared worker eps (FO_EPS_SHARED_WORKERS, a variant the paper does not have).  When every worker
  * uses the same eps_t and the same amplitude, linearity of H^T turns the server's M decodes into one:

@@ -146,6 +146,7 @@ struct fo_plan {
     float *scales_up;    // [M][nblocks]
     uint64_t *bits_down; // [planes][W]
     float *scales_down;  // [nblocks]
+    unsigned long long *blk_sums; // [nblocks] integer sums of squares (all-shared eps with the measured-norm rule)
     fo_stats *stats;     // device, optional
     const unsigned long long *round_dev; // device, set for the duration of fo_step_dev_round
     Profiler prof;
@@ -168,7 +169,6 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     if (!(q.alpha >= 2.f) || !(q.alpha_s >= 2.f)) return FO_EINVAL;
     if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
     if (q.server_scale != FO_SERVER_SCALE_THM && q.server_scale != FO_SERVER_SCALE_L2) return FO_EINVAL;
-    if (q.server_scale == FO_SERVER_SCALE_L2 && q.eps_mode == FO_EPS_SHARED_ALL) return FO_EINVAL;
 
     fo_plan *pl = new (std::nothrow) fo_plan();
     if (!pl) return FO_ENOMEM;
@@ -214,7 +214,8 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     const size_t sz_part = up((size_t)q.M * pl->ntiles * 4);
     const size_t sz_bu = up((size_t)q.M * pl->W * 8), sz_su = up((size_t)q.M * pl->nblocks * 4);
     const size_t sz_bd = up((size_t)pl->planes * pl->W * 8), sz_sd = up(pl->nblocks * 4);
-    pl->scratch_bytes = sz_a + sz_b + sz_c + sz_part + sz_bu + sz_su + sz_bd + sz_sd;
+    const size_t sz_bs = up(pl->nblocks * 8);
+    pl->scratch_bytes = sz_a + sz_b + sz_c + sz_part + sz_bu + sz_su + sz_bd + sz_sd + sz_bs;
     void *mem = nullptr;
     hipError_t e = hipMalloc(&mem, pl->scratch_bytes);
     if (e != hipSuccess) {
@@ -231,7 +232,8 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     pl->bits_up = reinterpret_cast<uint64_t *>(c); c += sz_bu;
     pl->scales_up = reinterpret_cast<float *>(c); c += sz_su;
     pl->bits_down = reinterpret_cast<uint64_t *>(c); c += sz_bd;
-    pl->scales_down = reinterpret_cast<float *>(c);
+    pl->scales_down = reinterpret_cast<float *>(c); c += sz_sd;
+    pl->blk_sums = reinterpret_cast<unsigned long long *>(c);
     *out = pl;
     return FO_OK;
 }
@@ -288,6 +290,7 @@ inline bool args_ok(const ShallArgs &z, int)
 {
     return z.bits_up && z.dst && z.lam && z.lam_s && z.M >= 1 && z.M <= FO_MAX_WORKERS && z.K >= 1 && z.planes >= 1;
 }
+inline bool args_ok(const ShallArgs &z, unsigned long long *sums, int kid) { return sums && args_ok(z, kid); }
 inline bool args_ok(const ServerTileArgs &s, int)
 {
     return s.enc.src && s.bits_up && s.scales_up && s.M >= 1 && s.M <= FO_MAX_WORKERS && s.enc.S >= 6 && s.enc.S <= 15;
@@ -546,6 +549,13 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         z.bits_up = bits_up; z.dst = bits_down; z.lam = scales_up; z.lam_s = scales_down;
         z.W = pl->W; z.logb = pl->logb; z.M = M; z.K = pl->p.K; z.planes = pl->planes; z.dither = pl->p.dither;
         z.k0 = r.k0; z.k1 = r.k1; z.round_lo = r.round_lo; z.round_dev = r.round_dev; z.sqrtb = pl->sqrtb;
+        if (l2s) { // lambda^s from ||gbar||: an exact integer count first
+            const dim3 bg((unsigned)((pl->nblocks + 255) / 256));
+            FO_TRY(launch(pl, KID_SCALES, k_zero_u64, bg, dim3(256), st, pl->blk_sums, pl->nblocks));
+            FO_TRY(launch(pl, KID_SHALL, k_shall_sumsq, dim3((unsigned)((pl->W + 15) / 16)), dim3(256), st, z, pl->blk_sums));
+            FO_TRY(launch(pl, KID_SCALES, k_shall_scales, bg, dim3(256), st, pl->blk_sums, scales_up, pl->nblocks, M,
+                          pl->coef_lambda_s, scales_down));
+        }
         FO_TRY(launch(pl, KID_SHALL, k_shall, dim3((unsigned)((pl->W + 15) / 16)), dim3(256), st, z));
         if (!gbar_or_null) return FO_OK;
         // the mean itself was asked for (checking): one inverse transform of the summed sign vectors, below

@@ -21,6 +21,67 @@ struct ShallArgs {
     float sqrtb;               // the kernels compare in the unnormalised domain: values and thresholds times sqrt(b)
 };
 
+// ---- measured-norm server amplitude for this mode: ||gbar_block||^2 = (lambda / M)^2 sum_i (2 c_i - M)^2, and the
+// sum is an integer, so it is accumulated exactly (and in any order) with 64-bit integer atomics.
+__global__ void k_zero_u64(unsigned long long *p, uint64_t n)
+{
+    const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
+// Same fetch-and-count as k_shall; sums[j] += sum over block j of (2 c - M)^2.
+__global__ __launch_bounds__(256) void k_shall_sumsq(const ShallArgs a, unsigned long long *sums)
+{
+    __shared__ unsigned long long part[16];
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const uint64_t q = (uint64_t)blockIdx.x * 4u + wave;
+    int32_t c[4] = { 0, 0, 0, 0 };
+    if (4 * q < a.W) {
+        for (uint32_t m0 = 0; m0 < a.M; m0 += 16u) {
+            const uint32_t m = m0 + (lane >> 2);
+            const uint64_t w = 4 * q + (lane & 3u);
+            const uint64_t mine = (m < a.M && w < a.W) ? a.bits_up[(uint64_t)m * a.W + w] : 0ull;
+            const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
+#pragma unroll
+            for (int i = 0; i < 64; ++i) {
+                const uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine_hi, i) << 32) |
+                                      (uint32_t)__builtin_amdgcn_readlane((int)mine_lo, i);
+                c[i & 3] += __builtin_amdgcn_inverse_ballot_w64(word) ? 1 : 0;
+            }
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const bool live = 4 * q + s < a.W;
+        const int32_t v = live ? 2 * c[s] - (int32_t)a.M : 0;
+        uint32_t sq = (uint32_t)(v * v); // at most 64^2 per lane
+#pragma unroll
+        for (int k = 1; k < 64; k <<= 1) sq += __shfl_xor(sq, k, 64);
+        if (lane == 0) part[wave * 4 + s] = sq;
+    }
+    __syncthreads();
+    if (a.logb >= 10u) {
+        // the workgroup's 1024 coordinates lie in one block: one atomic for all of them
+        if (threadIdx.x == 0) {
+            unsigned long long tot = 0;
+            for (int i = 0; i < 16; ++i) tot += part[i];
+            const uint64_t w0 = (uint64_t)blockIdx.x * 16u;
+            if (w0 < a.W) atomicAdd(sums + ((w0 * 64u) >> a.logb), tot);
+        }
+    } else if (threadIdx.x < 16u) {
+        const uint64_t w = (uint64_t)blockIdx.x * 16u + threadIdx.x;
+        if (w < a.W) atomicAdd(sums + ((w * 64u) >> a.logb), part[threadIdx.x]);
+    }
+}
+
+// lambda^s_j = coef * (lambda_j / M) * sqrt(sums[j]),  coef = alpha_s sqrt(ln b / b)
+__global__ void k_shall_scales(const unsigned long long *sums, const float *lam, uint64_t nblocks, uint32_t M, float coef,
+                               float *lam_s)
+{
+    const uint64_t j = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
+    if (j < nblocks) lam_s[j] = coef * (lam[j] / (float)M) * (float)sqrt((double)sums[j]);
+}
+
 __global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
 {
     const uint32_t lane = threadIdx.x & 63u;

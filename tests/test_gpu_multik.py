@@ -101,6 +101,11 @@ def test_second_moment_falls_as_one_over_K(env):
     ("shared_eps_single_pass", 9_000, 3, 0, dict(eps_mode=1)),
     ("three_pass", (1 << 25) + 5, 1, 0, {}),
     ("n2p25", 25_557_032, 2, 0, {}),
+    ("all_shared_single_pass", 9_000, 3, 0, dict(eps_mode=2)),
+    ("all_shared_blocked_small", 7_000, 5, 6, dict(eps_mode=2)),
+    ("all_shared_blocked_128", 7_000, 4, 7, dict(eps_mode=2)),
+    ("all_shared_blocked_512", 70_000, 3, 9, dict(eps_mode=2)),
+    ("all_shared_two_pass_K2", 200_000, 16, 0, dict(eps_mode=2, K=2)),
 ])
 def test_measured_norm_server_amplitude(env, name, d, M, blk, kw):
     """FO_SERVER_SCALE_L2: lambda^s = alpha_s sqrt(ln b / b) ||gbar_block|| from the mean the server has just formed."""
