@@ -340,3 +340,32 @@ def test_per_kernel_timing(env):
     with pytest.raises(B.FoError):
         plan.fo_profile_end()          # not recording any more
     plan.close()
+
+
+def test_resume_needs_only_x_and_the_round(env):
+    """The codec keeps no state between rounds (eps and dither are functions of seed, round, party, coordinate):
+    a run that is cut after round 3 and continued by a fresh plan from the saved iterate and round number ends where
+    the uninterrupted run ends."""
+    import torch
+    O, B, inputs, dev = env
+    d, M = 200_000, 3
+    gs = [torch.from_numpy(inputs.gaussian(d, m)).to(dev) for m in range(M)]
+    whole = B.Plan(d=d, M=M, seed=17)
+    x = torch.zeros(d, dtype=torch.float32, device=dev)
+    for r in range(7):
+        whole.fo_step(gs, x, 0.01, r)
+    first = B.Plan(d=d, M=M, seed=17)
+    y = torch.zeros(d, dtype=torch.float32, device=dev)
+    for r in range(4):
+        first.fo_step(gs, y, 0.01, r)
+    torch.cuda.synchronize()
+    saved = y.cpu()                       # the checkpoint: iterate and round number
+    first.close()
+    second = B.Plan(d=d, M=M, seed=17)
+    z = saved.to(dev)
+    for r in range(4, 7):
+        second.fo_step(gs, z, 0.01, r)
+    torch.cuda.synchronize()
+    assert torch.equal(z, x)
+    whole.close()
+    second.close()

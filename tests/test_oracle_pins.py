@@ -504,3 +504,21 @@ def test_block_range_equals_full(oracle):
     dec = oracle.decode(p, full["q"], full["lam"], 2, 1)
     decp = oracle.decode_blocks(p, full["q"][64 * 5:64 * 9], full["lam"][5:9], 2, 1, j0=5, nj=4)
     assert np.array_equal(decp, dec[64 * 5:64 * 9])
+
+
+def test_oracle_is_clean_under_host_sanitizers(tmp_path):
+    """The oracle, driven through whole rounds on exactly sized arrays, under AddressSanitizer and
+    UndefinedBehaviorSanitizer (host only): no out-of-bounds access, no undefined operation."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "orc_selftest")
+    cc = subprocess.run(["gcc", "-std=c11", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                         "-static-libasan", "-static-libubsan", "-o", exe, os.path.join(root, "oracle", "selftest.c"), "-lm", "-lpthread"],
+                        capture_output=True, text=True)
+    if cc.returncode != 0 and "sanitize" in cc.stderr:
+        pytest.skip("this gcc has no sanitizer runtime")
+    assert cc.returncode == 0, cc.stderr
+    run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert run.stdout.count("checksum") == 5
