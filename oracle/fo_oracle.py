@@ -31,6 +31,12 @@ def build(force: bool = False) -> str:
         subprocess.check_call(
             ["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC,
              "-lm", "-lpthread"])
+        # the self-test driver (run under sanitizers by the CPU tests) must at least compile with the library
+        out_dir = os.path.join(os.path.dirname(_SRC), "_build")
+        os.makedirs(out_dir, exist_ok=True)
+        subprocess.check_call(
+            ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-o", os.path.join(out_dir, "orc_selftest"),
+             os.path.join(os.path.dirname(_SRC), "selftest.c"), "-lm", "-lpthread"])
     return _LIB
 
 
