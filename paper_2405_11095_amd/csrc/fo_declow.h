@@ -43,9 +43,11 @@ constexpr uint32_t walsh_mask32(int j)
 // second call does by itself when xa and xb differ.
 template <int SC>
 __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xa,
-                                            uint32_t *xb, s16x2 (&v)[32])
+                                            uint32_t *xb, s16x2 (&v)[32], const uint32_t t = threadIdx.x)
 {
-    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    // t: the thread index; a caller that loops may pass a copy the compiler cannot see through, so that the
+    // offsets derived from it are recomputed per call instead of being kept in registers across the loop
+    const uint32_t lane = t & 63u, wave = t >> 6;
     const uint32_t S = SC ? (uint32_t)SC : S_arg;
 
     // ------------------------------------------------------------------ stages b0..b4 (layout LA)

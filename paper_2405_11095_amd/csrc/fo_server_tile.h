@@ -61,7 +61,9 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
             lam[t] = gb < a.nblocks ? sa.scales_up[(uint64_t)m * a.nblocks + gb] * sa.coef : 0.f;
         }
         s16x2 v[32];
-        declow_tile<0>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, xbuf, v);
+        uint32_t tl = t;
+        asm volatile("" : "+v"(tl));
+        declow_tile<0>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, xbuf, v, tl);
         __syncthreads(); // the exchange buffer is read; the next worker's first exchange may write it
         // the table addresses are recomputed for every worker: hoisted out of the loop they would hold 64 registers
         // next to the 64 accumulators
