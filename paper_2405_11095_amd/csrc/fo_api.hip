@@ -1,5 +1,6 @@
 // C ABI of the FO-SGD codec (declared in include/fo.h): argument checks, plan scratch and kernel
-// launch sequences.  Every step of the codec runs in the kernels of fo_contig.h / fo_strided.h.
+// launch sequences.  Every step of the codec runs in the kernels of fo_contig.h, fo_strided.h, fo_declow.h,
+// fo_server_tile.h and fo_shall.h.
 #include <hip/hip_runtime.h>
 
 #include <cmath>

@@ -2,15 +2,16 @@
 // (transform lengths above 2^15).  A tile is R = 2^hb rows by 2^(15-hb) consecutive columns, rows
 // 2^ls coordinates apart; the stages act along the rows' axis only.
 //
-// Tile coordinate u = row << cb | col (cb = 15 - hb >= 5).  512 threads hold 64 values each, as 32
-// pairs of neighbouring columns, so every global access moves a pair: 8 bytes per lane for fp32,
-// 4 bytes per lane for the int16 intermediate that the decode side reads.
-//   LA (loads):              reg0 = u0  lanes = (u1..u6)  waves = (u7,u8,u9)     regs 1..5 = (u10..u14)
-//   LB (after the exchange): reg0 = u0  lanes = (u1..u6)  waves = (u10,u11,u12)  regs 1..5 = (u7,u8,u9,u13,u14)
-// The exchange swaps the wave bits with register bits 1..3 through LDS in two halves (register
-// bit 5 picks the half); lanes keep their bits, so LDS traffic is 8 bytes per lane, conflict free,
-// and stores are as coalesced as loads.  Row bits that fall on lane bits 4 and 5 (hb >= 9) are
-// handled with v_permlane16_swap / v_permlane32_swap.
+// Tile coordinate u = row << cb | col (cb = 15 - hb >= 5).  A thread holds 2^LV values as pairs of
+// neighbouring columns (LV = 6: 512 threads x 64 values; LV = 5: 1024 threads x 32 values), so every global
+// access moves a pair: 8 bytes per lane for fp32, 4 bytes per lane for the int16 intermediate that the decode
+// side reads.  With NW = 9 - LV wave bits (see SL<LV>):
+//   LA (loads):              reg0 = u0  lanes = (u1..u6)  waves = (u7..u6+NW)      regs 1.. = (u7+NW..u14)
+//   LB (after the exchange): reg0 = u0  lanes = (u1..u6)  waves = (u7+NW..u6+2NW)  regs 1..NW = (u7..u6+NW)
+// The exchange swaps the wave bits with register bits 1..NW through LDS (in two halves, one per pair member;
+// the server pass does it in one whole-tile pass); lanes keep their bits, so LDS accesses are conflict free and
+// stores are as coalesced as loads.  Row bits that fall on lane bits 4 and 5 (hb >= 9) are handled with
+// v_permlane16_swap / v_permlane32_swap.
 // Modes
 //   SM_ENC_FIRST : fp32 gradient (zero padded), eps flip on load, tile sum of squares -> fp32 intermediate
 //   SM_DEC_LAST  : integer intermediate -> lambda/sqrt(b) scaling, eps flip, store / SGD update (Def. 3.8)
