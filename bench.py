@@ -129,7 +129,9 @@ def main():
     W8 = n // 8
     per_step = {
         "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
-        "k_contig<IN_F32,OUT_PACK>": (M + 1) * (4 * n + W8),
+        # with blocks of 2^16 the workers' encode is one pass (k_contig_pair); only the server re-encodes in two
+        "k_contig<IN_F32,OUT_PACK>": ((M + 1) if "k_contig_pair" not in per_kernel else 1) * (4 * n + W8),
+        "k_contig_pair": M * (4 * d + W8),
         "k_declow": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,

@@ -103,13 +103,14 @@ enum KernelId {
     KID_COUNT_LOW,      // k_contig<IN_COUNT,*>
     KID_SERVER_TILE,    // k_mean_tile
     KID_SHALL,          // k_shall
+    KID_ENC_PAIR,       // k_contig_pair
     KID_SCALES,         // k_finalize_scales / k_fill_scales / k_server_scales
     KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_tile", "k_shall", "scale kernels",
+    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_tile", "k_shall", "k_contig_pair", "scale kernels",
 };
 
 struct Profiler {
@@ -276,10 +277,11 @@ Rng rng_of(const fo_plan *pl, uint64_t round)
 // Host-side guard against launching a kernel with a pointer it will dereference left unset.
 inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
 {
-    const bool grad_in = kid == KID_ENC_SINGLE;
+    const bool grad_in = kid == KID_ENC_SINGLE || kid == KID_ENC_PAIR;
     if (!c.dst) return false;
+    if (kid == KID_ENC_PAIR && (c.logb != 16 || c.S != 15)) return false;
     if (grad_in ? (c.use_tab ? !tab.p[0] : !c.src) : !c.src) return false;
-    const bool needs_scales = kid == KID_ENC_SINGLE || kid == KID_ENC_LOW || kid == KID_DEC_SINGLE;
+    const bool needs_scales = kid == KID_ENC_SINGLE || kid == KID_ENC_PAIR || kid == KID_ENC_LOW || kid == KID_DEC_SINGLE;
     if (kid == KID_COUNT_LOW && (c.M < 1 || c.M > FO_MAX_WORKERS)) return false;
     return !needs_scales || c.scales != nullptr;
 }
@@ -364,6 +366,19 @@ int launch_pack(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigArg
 {
     if (c.stat_clipped) return launch_pack_s<IN, true>(pl, kid, grid, st, c, tab);
     return launch_pack_s<IN, false>(pl, kid, grid, st, c, tab);
+}
+
+// Encode of blocks of 2^16 coordinates in one pass.
+int launch_pair(fo_plan *pl, dim3 grid, hipStream_t st, const ContigArgs &c, const PtrTab &tab)
+{
+    const bool dither = c.dither == FO_DITHER_UNIFORM;
+    const dim3 block(2 * kThreads);
+    if (c.K > 1) {
+        if (dither) return launch(pl, KID_ENC_PAIR, k_contig_pair<true, true>, grid, block, st, c, tab);
+        return launch(pl, KID_ENC_PAIR, k_contig_pair<false, true>, grid, block, st, c, tab);
+    }
+    if (dither) return launch(pl, KID_ENC_PAIR, k_contig_pair<true, false>, grid, block, st, c, tab);
+    return launch(pl, KID_ENC_PAIR, k_contig_pair<false, false>, grid, block, st, c, tab);
 }
 
 StridedArgs strided_base(const fo_plan *pl, const Rng &r, uint32_t pass)
@@ -453,6 +468,21 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
         }
         FO_TRY(launch_pack<IN_GRAD>(pl, KID_ENC_SINGLE, grid, st, c, tb));
         return FO_OK;
+    }
+    if (pl->logb == 16 && !c.stat_clipped) {
+        // blocks of exactly two tiles: one pass, a workgroup of 1024 threads per block
+        c.src = src; c.src_stride = src_stride; c.use_tab = tab ? 1u : 0u;
+        c.len_in = len_in;
+        c.compute_scale = scales_given ? 0u : 1u;
+        const dim3 pgrid((unsigned)(pl->ntiles / 2), nslots);
+        if (common && !scales_given) {
+            c.scales_only = 1u;
+            FO_TRY(launch_pair(pl, pgrid, st, c, tb));
+            FO_TRY(launch(pl, KID_SCALES, k_common_scales, cgrid, dim3(256), st, scales, pl->nblocks, nslots));
+            c.scales_only = 0u;
+            c.compute_scale = 0u;
+        }
+        return launch_pair(pl, pgrid, st, c, tb);
     }
     // transform lengths above 2^15: high stages first (eps flip and norm on load), low stages last
     const uint32_t first = pl->npass - 1;

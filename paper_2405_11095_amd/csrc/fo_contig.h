@@ -76,18 +76,28 @@ struct ContigArgs {
 // c_i = #{k < K : z_i + tau_{k,i} >= 0} in {0..K}, i.e. q_i = 2 c_i - K = (K / lambda) Q_{lambda,K}(z)_i, stored as
 // `planes` bit planes of W words each (plane p holds bit p of every c_i).  OUT_PACK draws K dithers per
 // coordinate and writes the planes; IN_BITS reads them.  K = 1 is the plain sign message and uses MULTIK = false.
-// The work of one workgroup on tile `tile` of party slot `slot`; lds has kLdsWords words.
-template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK, bool STATS = false>
+// The work of 512 threads (t = 0..511) on tile `tile` of party slot `slot`; lds has kLdsWords words.
+// PAIR (gradient in, transform length exactly 2^16): two such groups of 512 threads in one workgroup take the two
+// tiles of a block; lds_partner is the other group's LDS.  The stage on bit 15 pairs coordinate i of the lower
+// tile with coordinate i of the upper one, and it can go first: each group loads and flips its own tile, the two
+// swap their values through LDS, the lower forms x_lo + x_hi and the upper x_lo - x_hi, and each runs the fifteen
+// remaining stages on its own tile as usual.  The 2^16-point transform then costs one pass over memory instead
+// of two.  The block's norm is the sum of the two groups' partial sums.
+template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK, bool STATS = false, bool PAIR = false>
 __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &tab, const uint32_t tile, const uint32_t slot,
-                                            uint32_t *const lds)
+                                            uint32_t *const lds, const uint32_t t, uint32_t *const lds_partner = nullptr)
 {
+    static_assert(!PAIR || (IN == IN_GRAD && OUT == OUT_PACK && SC == 15 && !SMALLB), "pair mode: gradient in, bits out");
     using T = typename std::conditional<(IN == IN_BITS || IN == IN_COUNT), int32_t, float>::type;
     uint32_t *const xbuf = lds;
     uint32_t *const epsw = lds + kXWords;
     float *const lam = reinterpret_cast<float *>(lds + kXWords + kEpsWords);
     float *const red = reinterpret_cast<float *>(lds + kXWords + kEpsWords + kLamWords);
+    // PAIR: the partial sums of the block's lower and upper tile, so that both groups add them in the same order
+    const float *const red_lo = PAIR ? reinterpret_cast<const float *>(((tile & 1u) ? lds_partner : lds) + kXWords + kEpsWords + kLamWords) : nullptr;
+    const float *const red_hi = PAIR ? reinterpret_cast<const float *>(((tile & 1u) ? lds : lds_partner) + kXWords + kEpsWords + kLamWords) : nullptr;
 
-    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t lane = t & 63u, wave = t >> 6;
     const uint64_t base = (uint64_t)tile << kTileLog2;
     const uint32_t S = SC ? (uint32_t)SC : a.S;
     const uint32_t party = (a.party0 == 0xFFFFFFFFu) ? a.party0 : a.party0 + slot;
@@ -201,6 +211,16 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
         if (a.scales_only) {
             // amplitudes only (used to agree on a common amplitude before any worker quantises)
             __syncthreads();
+            if constexpr (PAIR) {
+                if (t == 0 && !(tile & 1u)) {
+                    float s = 0.f;
+                    for (uint32_t k = 0; k < 8u; ++k) s += red_lo[k];
+                    for (uint32_t k = 0; k < 8u; ++k) s += red_hi[k];
+                    const uint64_t gb = base >> 16;
+                    if (gb < a.nblocks) a.scales[slot * a.scales_stride + gb] = a.coef_lambda * sqrtf(s);
+                }
+                return;
+            }
             const uint32_t nblk = kTile >> S;
             if (t < nblk) {
                 const uint64_t gb = (uint64_t)tile * nblk + t;
@@ -229,6 +249,31 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
             const uint32_t nib = epsw[wave * 128u + c * 8u + (lane >> 3)] >> ((lane & 7u) * 4u);
 #pragma unroll
             for (int k = 0; k < 4; ++k) v[4 * c + k] = flip_by_bit31(v[4 * c + k], nib << (31 - k));
+        }
+        if constexpr (PAIR) {
+            // stage b15 across the two groups, sixteen values per thread and round.  Two buffers in turn: the
+            // barrier of round g+1 comes after every thread's reads of round g, so round g+2 may overwrite them.
+            const uint32_t upper = tile & 1u;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float4 *const mine = reinterpret_cast<float4 *>(xbuf + (g & 1) * 8192u) + t;
+                const float4 *const theirs = reinterpret_cast<const float4 *>(lds_partner + (g & 1) * 8192u) + t;
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    mine[c * 512] = make_float4(v[16 * g + 4 * c], v[16 * g + 4 * c + 1], v[16 * g + 4 * c + 2], v[16 * g + 4 * c + 3]);
+                __syncthreads();
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float4 o = theirs[c * 512];
+                    const float ov[4] = { o.x, o.y, o.z, o.w };
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        float &x = v[16 * g + 4 * c + k];
+                        x = upper ? ov[k] - x : x + ov[k];
+                    }
+                }
+            }
+            __syncthreads(); // the last reads are done before the first exchange of the transform writes xbuf
         }
     }
 
@@ -275,7 +320,11 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
             const uint64_t gb = blk0 + t;
             if (IN == IN_GRAD && a.compute_scale) {
                 float s;
-                if (S <= 12u) {
+                if constexpr (PAIR) {
+                    s = 0.f;
+                    for (uint32_t k = 0; k < 8u; ++k) s += red_lo[k];
+                    for (uint32_t k = 0; k < 8u; ++k) s += red_hi[k];
+                } else if (S <= 12u) {
                     s = red[t];
                 } else {
                     const uint32_t per = 1u << (S - 12u);
@@ -283,7 +332,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
                     for (uint32_t k = 0; k < per; ++k) s += red[t * per + k];
                 }
                 l = a.coef_lambda * sqrtf(s);
-                if (gb < a.nblocks) a.scales[slot * a.scales_stride + gb] = l;
+                if (gb < a.nblocks && !(PAIR && (tile & 1u))) a.scales[slot * a.scales_stride + gb] = l;
             } else if (gb < a.nblocks) {
                 l = a.scales[slot * a.scales_stride + gb];
             }
@@ -497,7 +546,17 @@ template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0,
 __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
 {
     __shared__ uint32_t lds[kLdsWords];
-    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK, STATS>(a, tab, blockIdx.x, blockIdx.y, lds);
+    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK, STATS>(a, tab, blockIdx.x, blockIdx.y, lds, threadIdx.x);
+}
+
+// Encode of blocks of exactly 2^16 coordinates in one pass: 1024 threads, one block (two tiles) per workgroup.
+template <bool DITHER, bool MULTIK>
+__global__ __launch_bounds__(2 * kThreads) void k_contig_pair(const ContigArgs a, const PtrTab tab)
+{
+    __shared__ uint32_t lds[2 * kLdsWords];
+    const uint32_t h = threadIdx.x >> 9;
+    contig_tile<IN_GRAD, OUT_PACK, DITHER, false, 15, MULTIK, false, true>(a, tab, 2u * blockIdx.x + h, blockIdx.y, lds + h * kLdsWords,
+                                                                           threadIdx.x & 511u, lds + (h ^ 1u) * kLdsWords);
 }
 
 } // namespace fo

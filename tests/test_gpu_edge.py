@@ -97,12 +97,15 @@ def test_repeat_encodes_agree_large(env):
     ("bound_rule", dict(scale_rule=0, Bnorm=400.0)),
     ("no_dither", dict(dither=1)),
     ("alpha3", dict(alpha=3.0, alpha_s=2.5)),
+    ("bound_rule_b65536", dict(scale_rule=0, Bnorm=400.0, block_log2=16)),
+    ("no_dither_b65536", dict(dither=1, block_log2=16)),
 ])
 def test_parameter_variants(env, name, kw):
     O, B, inputs, dev = env
     d, M = 150_000, 3
     gs = [inputs.gaussian(d, m) for m in range(M)]
-    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=0, seed=77, rnd=2, delta=0.1, device=dev, **kw)
+    kw = dict(kw)
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=kw.pop("block_log2", 0), seed=77, rnd=2, delta=0.1, device=dev, **kw)
     print(name, rep, flush=True)
     gates(rep)
 
@@ -112,6 +115,7 @@ def test_parameter_variants(env, name, kw):
     ("blocked_small", 7_000, 3, 7, 1),
     ("blocked", 200_003, 4, 12, 3),
     ("two_pass", (1 << 18) + 11, 7, 0, 1),
+    ("blocked_b65536", (1 << 18) + 11, 3, 16, 2),
     ("n2p25", 25_557_032, 3, 0, 1),
 ])
 def test_all_shared_eps_zero_transform_server(env, name, d, M, blk, K):
@@ -214,6 +218,7 @@ def test_c4_full_size_sampled_blocks(env, blk):
     ("single_pass", 30_000, 5, 0),
     ("blocked", 200_003, 4, 12),
     ("two_pass", (1 << 18) + 11, 7, 0),
+    ("blocked_b65536", (1 << 18) + 11, 5, 16),
     ("n2p25", 25_557_032, 3, 0),
 ])
 def test_shared_worker_eps_popcount_server(env, name, d, M, blk):

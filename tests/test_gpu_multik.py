@@ -38,7 +38,7 @@ def test_round_trip_with_averaged_downlink(env, name, d, M, blk, K, kw):
     P.gates(rep)
 
 
-@pytest.mark.parametrize("d,blk,K", [(50_000, 0, 4), (9_000, 8, 6)])
+@pytest.mark.parametrize("d,blk,K", [(50_000, 0, 4), (9_000, 8, 6), (150_000, 16, 3)])
 def test_server_party_encode_and_decode(env, d, blk, K):
     """fo_encode / fo_decode for the server party use the K-fold quantiser on their own as well."""
     import torch

@@ -41,6 +41,9 @@ CASES = [
     ("blocked_b16384", (1 << 18) + 77, 2, 14, "layered"),
     ("blocked_b32768", 100_000, 2, 15, "gaussian"),
     ("blocked_b65536", (1 << 19) + 5, 2, 16, "layered"),
+    # blocks of two tiles: the last block's upper tile partly filled, then its lower tile partly filled
+    ("blocked_b65536_upper_ragged", (1 << 16) + 40_000, 3, 16, "heavy"),
+    ("blocked_b65536_lower_ragged", (1 << 17) + 9_999, 2, 16, "gaussian"),
     # the benchmark's geometry (n = 2^25: ten strided stages, the specialised kernels), fewer workers
     ("c3_geometry_n2p25", 25_557_032, 3, 0, "heavy"),
 ]
