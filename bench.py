@@ -132,7 +132,7 @@ def main():
         # with blocks of 2^16 the workers' encode is one pass (k_contig_pair); only the server re-encodes in two
         "k_contig<IN_F32,OUT_PACK>": ((M + 1) if "k_contig_pair" not in per_kernel else 1) * (4 * n + W8),
         "k_contig_pair": M * (4 * d + W8),
-        "k_declow": ((M + 1) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
+        "k_declow": ((M + (0 if "k_decode_pair" in per_kernel else 1)) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_mean_tile": M * W8 + 4 * n,
@@ -140,6 +140,7 @@ def main():
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
         "k_decode_tile": W8 + 8 * d,
+        "k_decode_pair": W8 + 8 * d,
     }
     step_bytes = per_step.get(dom)
     bytes_per_launch = step_bytes * args.steps / launches if step_bytes else None

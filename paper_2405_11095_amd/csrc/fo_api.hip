@@ -104,13 +104,14 @@ enum KernelId {
     KID_SERVER_TILE,    // k_mean_tile
     KID_SHALL,          // k_shall
     KID_ENC_PAIR,       // k_contig_pair
+    KID_DEC_PAIR,       // k_decode_pair
     KID_SCALES,         // k_finalize_scales / k_fill_scales / k_server_scales
     KID_COUNT
 };
 const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_tile", "k_shall", "k_contig_pair", "scale kernels",
+    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_tile", "k_shall", "k_contig_pair", "k_decode_pair", "scale kernels",
 };
 
 struct Profiler {
@@ -287,6 +288,7 @@ inline bool args_ok(const ContigArgs &c, const PtrTab &tab, int kid)
 }
 inline bool args_ok(const ContigArgs &c, int kid) // k_declow, k_decode_tile
 {
+    if (kid == KID_DEC_PAIR) return c.src && c.dst && c.scales && c.logb == 16;
     return c.src && c.dst && (kid != KID_DEC_SINGLE || (c.scales && c.S >= 6 && c.S <= 15));
 }
 inline bool args_ok(const ShallArgs &z, int)
@@ -529,6 +531,11 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
         if (multik) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 0, true>), grid, block, st, c, none));
         else FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile, grid, block, st, c));
         return FO_OK;
+    }
+    if (pl->logb == 16 && !multik) {
+        // blocks of exactly two tiles: one pass, a workgroup of 1024 threads per block
+        c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
+        return launch(pl, KID_DEC_PAIR, k_decode_pair, dim3((unsigned)(pl->ntiles / 2), 1), dim3(2 * kThreads), st, c);
     }
     c.dst = tmp; c.dst_stride = 0;
     StridedArgs s = strided_base(pl, r, pl->npass - 1);

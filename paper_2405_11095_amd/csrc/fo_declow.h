@@ -41,12 +41,12 @@ constexpr uint32_t walsh_mask32(int j)
 // may be the same buffer.  The second exchange starts with a barrier (all earlier reads of xb are over) and its
 // reads are not followed by one: a caller that loops must not write xb again before its next barrier, which a
 // second call does by itself when xa and xb differ.
+// declow_front: up to the point where the tile sits in xb in layout LB and the barrier after it has been passed;
+// declow_back: the read into layout LC and the last three stages.  declow_tile is the two in a row.
 template <int SC>
-__device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xa,
-                                            uint32_t *xb, s16x2 (&v)[32], const uint32_t t = threadIdx.x)
+__device__ __forceinline__ void declow_front(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xa,
+                                             uint32_t *xb, s16x2 (&v)[32], const uint32_t t)
 {
-    // t: the thread index; a caller that loops may pass a copy the compiler cannot see through, so that the
-    // offsets derived from it are recomputed per call instead of being kept in registers across the loop
     const uint32_t lane = t & 63u, wave = t >> 6;
     const uint32_t S = SC ? (uint32_t)SC : S_arg;
 
@@ -94,6 +94,13 @@ __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, u
         for (int r = 0; r < 32; ++r) xb[wofs + r * 16] = __builtin_bit_cast(uint32_t, v[r]);
     }
     __syncthreads();
+}
+
+template <int SC>
+__device__ __forceinline__ void declow_back(const uint32_t *xb, uint32_t S_arg, s16x2 (&v)[32], const uint32_t t)
+{
+    const uint32_t lane = t & 63u, wave = t >> 6;
+    const uint32_t S = SC ? (uint32_t)SC : S_arg;
     {
         const uint32_t rofs = lane + wave * 256u + 16u * (wave >> 2);
 #pragma unroll
@@ -107,6 +114,58 @@ __device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, u
     // the popcount offset, gathered by the ten later stages on the coordinates with b5..b14 = 0
     if constexpr (SC == 15)
         if (t < 16u) v[0] -= s16x2{ 16384, 16384 };
+}
+
+template <int SC>
+__device__ __forceinline__ void declow_tile(const uint32_t *words, uint64_t W, uint32_t tile, uint32_t S_arg, uint32_t *xa,
+                                            uint32_t *xb, s16x2 (&v)[32], const uint32_t t = threadIdx.x)
+{
+    // t: the thread index; a caller that loops may pass a copy the compiler cannot see through, so that the
+    // offsets derived from it are recomputed per call instead of being kept in registers across the loop
+    declow_front<SC>(words, W, tile, S_arg, xa, xb, v, t);
+    declow_back<SC>(xb, S_arg, v, t);
+}
+
+// The back half for transforms of exactly 2^16 points, where two groups of 512 threads in one workgroup hold the
+// two tiles of a block (UPPER: the group with the upper tile).  Both have run declow_front<15>; xb_own and xb_oth
+// are their exchange buffers.  The sixteenth stage, on bit 15, pairs dword D of the lower tile with dword D of
+// the upper one, and it is done here, before the stages on b12..b14 (stages commute): each group reads both
+// buffers and keeps lo + hi (lower) or lo - hi (upper).  The results of all sixteen stages need 17 bits (half
+// values of up to 2^16 signs), so the last stage, b14, runs on int32; up to there packed int16 is exact (it
+// wraps, but every true value before the last stage fits).  Eight packed registers at a time: register group
+// G = (b7,b8) holds the registers r = q + 8 G, q = (b12,b13,b14), and emit(G, w) gets their values as
+// w[2 q + j], j = b0.  The popcount offset of 16 per input has grown to 16 * 2^10 on the coordinates with
+// b5..b13 = 0 of the lower tile before the last stage (it cancels in the upper tile) and is taken off there.
+template <bool UPPER, typename F>
+__device__ __forceinline__ void declow_pair_back(const uint32_t *xb_own, const uint32_t *xb_oth, const uint32_t t, F &&emit)
+{
+    const uint32_t lane = t & 63u, wave = t >> 6;
+    const uint32_t rofs = lane + wave * 256u + 16u * (wave >> 2);
+    static_for<4>([&](auto G) {
+        s16x2 v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t off = rofs + (G.value & 1) * 64 + (G.value >> 1) * 128 + q * (2048 + 32);
+            const s16x2 a = __builtin_bit_cast(s16x2, xb_own[off]), b = __builtin_bit_cast(s16x2, xb_oth[off]);
+            v[q] = UPPER ? b - a : a + b; // b15
+        }
+        bfly<s16x2, 0, 8>(v); // b12
+        bfly<s16x2, 1, 8>(v); // b13
+        if (!UPPER && G.value == 0 && t < 16u) {
+            v[0] -= s16x2{ 16384, 16384 };
+            v[4] -= s16x2{ 16384, 16384 };
+        }
+        int32_t w[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { // b14
+            const s16x2 a = v[q], b = v[q + 4];
+            w[2 * q] = (int32_t)a.x + (int32_t)b.x;
+            w[2 * q + 1] = (int32_t)a.y + (int32_t)b.y;
+            w[2 * (q + 4)] = (int32_t)a.x - (int32_t)b.x;
+            w[2 * (q + 4) + 1] = (int32_t)a.y - (int32_t)b.y;
+        }
+        emit(G, w);
+    });
 }
 
 // dword index (= coordinate / 2) inside the tile of register r of this thread in layout LC

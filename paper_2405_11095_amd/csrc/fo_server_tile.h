@@ -8,6 +8,11 @@
 //                  tile in the same kernel was measured slower: it needs so many registers that one 512-thread
 //                  workgroup fills a CU.)
 //   k_decode_tile: one party's decoder with store / accumulate / SGD update.
+//   k_decode_pair: the decoder for transforms of exactly 2^16 points: a workgroup of 1024 threads, two groups of
+//                  512 on the two tiles of a block, sixteenth stage through both groups' exchange buffers
+//                  (declow_pair_back).  One pass over the packed signs instead of an int16 intermediate and a
+//                  strided second pass.  (The same construction for the server's mean was measured no faster
+//                  than the two-pass path, whose second pass also starts the re-encode.)
 #pragma once
 #include "fo_declow.h"
 
@@ -149,6 +154,81 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
             else q -= a.delta * y0;
         }
     }
+}
+
+// Geometry of one group of a pair workgroup.
+struct PairGroup {
+    uint32_t h, t, lane, wave, tile;
+    uint64_t base;
+    uint32_t dt, eshift;
+};
+__device__ __forceinline__ PairGroup pair_group()
+{
+    PairGroup g;
+    g.h = __builtin_amdgcn_readfirstlane(threadIdx.x >> 9); // the same in every lane of a wave: branches on it are scalar
+    g.t = threadIdx.x & 511u;
+    g.lane = g.t & 63u;
+    g.wave = g.t >> 6;
+    g.tile = 2u * blockIdx.x + g.h;
+    g.base = (uint64_t)g.tile << kTileLog2;
+    g.dt = g.lane | (g.wave << 8);
+    g.eshift = (g.lane & 15u) << 1;
+    return g;
+}
+
+// k_decode_tile for transforms of exactly 2^16 points; same uses of the argument block.
+__global__ __launch_bounds__(2 * kThreads) void k_decode_pair(const ContigArgs a)
+{
+    __shared__ uint32_t lds[2 * (kXWords + kEpsWords)];
+    const PairGroup g = pair_group();
+    const uint32_t slot = blockIdx.y;
+    uint32_t *const xb_own = lds + g.h * kXWords;
+    const uint32_t *const xb_oth = lds + (g.h ^ 1u) * kXWords;
+    uint32_t *const epsw = lds + 2 * kXWords + g.h * kEpsWords;
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
+    const uint32_t eps_party = (a.eps_party0 >= 0xFFFFFFFEu) ? a.eps_party0 : a.eps_party0 + slot;
+    const uint64_t gb = g.base >> 16;
+
+    if (g.t < 256u) {
+        const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, eps_party };
+        uint32_t w[4];
+        philox((uint32_t)(g.base >> 7) + g.t, key_eps, w);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) epsw[g.t * 4u + j] = w[j];
+    }
+    const float lamc = gb < a.nblocks ? a.scales[slot * a.scales_stride + gb] * a.out_coef : 0.f;
+    const uint32_t cbits = __float_as_uint(lamc);
+    {
+        s16x2 v[32];
+        const uint32_t *words = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
+        declow_front<15>(words, a.W, g.tile, 15u, xb_own, xb_own, v, g.t); // its barriers publish the eps table
+    }
+    float2 *dst = reinterpret_cast<float2 *>(static_cast<float *>(a.dst) + g.base);
+    const uint64_t room = a.len_out > g.base ? a.len_out - g.base : 0; // valid coordinates of this tile
+    auto store = [&](auto G, const int32_t (&w)[16]) {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const uint32_t D = g.dt + declow_reg_dword(8 * decltype(G)::value + q);
+            const uint32_t e = epsw[D >> 4];
+            const float y0 = (float)w[2 * q] * __uint_as_float(((e >> g.eshift) << 31) | cbits);
+            const float y1 = (float)w[2 * q + 1] * __uint_as_float(((e >> (g.eshift + 1u)) << 31) | cbits);
+            if (2ull * D + 1 < room) {
+                float2 o = dst[D];
+                if (a.store_mode == STORE_SET) o = make_float2(y0, y1);
+                else if (a.store_mode == STORE_ACC) o = make_float2(o.x + y0, o.y + y1);
+                else o = make_float2(o.x - a.delta * y0, o.y - a.delta * y1);
+                dst[D] = o;
+            } else if (2ull * D < room) {
+                float &o = static_cast<float *>(a.dst)[g.base + 2ull * D];
+                if (a.store_mode == STORE_SET) o = y0;
+                else if (a.store_mode == STORE_ACC) o += y0;
+                else o -= a.delta * y0;
+            }
+        }
+    };
+    if (g.h) declow_pair_back<true>(xb_own, xb_oth, g.t, store);
+    else declow_pair_back<false>(xb_own, xb_oth, g.t, store);
 }
 
 } // namespace fo
