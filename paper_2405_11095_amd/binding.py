@@ -186,9 +186,9 @@ class Plan:
 
     def fo_profile_end(self):
         """{kernel name: (launches, total_ms)} for the kernels that ran since fo_profile_begin."""
-        out = (KernelTime * 16)()
+        out = (KernelTime * 32)()
         n = C.c_size_t()
-        rc = load_library().fo_profile_end(self._h, out, 16, C.byref(n))
+        rc = load_library().fo_profile_end(self._h, out, 32, C.byref(n))
         if rc:
             raise FoError(rc, "fo_profile_end")
         return {out[i].name.decode(): (out[i].launches, out[i].total_ms) for i in range(n.value)}
