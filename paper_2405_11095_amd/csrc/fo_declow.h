@@ -13,7 +13,8 @@
 // 2 popcount - 32, so the result of all fifteen stages fits int16 exactly.  The -16 is not applied per
 // value: a constant offset of 16 on every input of the remaining ten stages ends up as 16 * 2^10 on the
 // coordinates whose bits b5..b14 are all zero and nowhere else, and is taken off there at the end
-// (int16 arithmetic wraps, so the detour through the offset cannot lose anything).
+// (int16 arithmetic wraps, so the detour through the offset cannot lose anything; the library is built with
+// -fwrapv, which makes that wrap-around defined behaviour of the signed vector types).
 //
 // Index-bit choreography (dword = pair of coordinates, bits b1..b14):
 //   LA: regs = (b1,b2,b3,b4,b11)   lanes = (b5..b10)            waves = (b12,b13,b14)   stages b0..b4, b11
