@@ -110,6 +110,12 @@ int orc_eps(uint64_t seed, uint64_t round, uint32_t eps_party, uint64_t i)
     return ((memo.w[(i >> 5) & 3] >> (i & 31)) & 1u) ? -1 : +1;
 }
 
+/* eps_i for i = i0 .. i0 + n - 1 as +-1.0 (the same draws as orc_eps, one by one) */
+void orc_eps_fill(uint64_t seed, uint64_t round, uint32_t eps_party, uint64_t i0, uint64_t n, double *out)
+{
+    for (uint64_t k = 0; k < n; ++k) out[k] = (double)orc_eps(seed, round, eps_party, i0 + k);
+}
+
 /* u_i in (-1,1) so that tau_i = lambda * u_i (Def. 3.2): one generator call covers the four
  * coordinates i = 256*q + 64*s + l (s = 0..3) with counter = 64*q + l; coordinate i takes word s.
  * The top 24 bits r give u = (2r + 1 - 2^24) / 2^24. */
@@ -161,6 +167,19 @@ void orc_wht_dense(const double *x, double *y, uint64_t n)
         for (uint64_t j = 0; j < n; ++j)
             s += (__builtin_popcountll(i & j) & 1) ? -x[j] : x[j];
         y[i] = s;
+    }
+}
+
+/* Single entries of y = H x by the same entry formula: y[k] = sum_j (-1)^{popcount(idx[k] & j)} x[j].
+ * O(n) per entry; lets a test check a few coordinates of a transform too long to run whole. */
+void orc_wht_rows(const double *x, uint64_t n, const uint64_t *idx, uint64_t cnt, double *y)
+{
+    for (uint64_t k = 0; k < cnt; ++k) {
+        const uint64_t i = idx[k];
+        double s = 0.0;
+        for (uint64_t j = 0; j < n; ++j)
+            s += (__builtin_popcountll(i & j) & 1) ? -x[j] : x[j];
+        y[k] = s;
     }
 }
 

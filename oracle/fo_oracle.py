@@ -102,6 +102,14 @@ def eps(seed, rnd, eps_party, idx):
                     dtype=np.float64)
 
 
+def eps_fill(seed, rnd, eps_party, i0, n):
+    """eps_i for i = i0 .. i0 + n - 1 as an fp64 array of +-1."""
+    out = np.empty(int(n), dtype=np.float64)
+    lib().orc_eps_fill(C.c_uint64(seed), C.c_uint64(rnd), C.c_uint32(eps_party), C.c_uint64(i0), C.c_uint64(n),
+                       _p(out, C.c_double))
+    return out
+
+
 def dither_u(seed, rnd, party, k, idx):
     L = lib()
     return np.array([L.orc_dither_u(seed, rnd, party, k, int(i)) for i in np.atleast_1d(idx)],
@@ -124,6 +132,17 @@ def wht_dense(x):
     x = _f64(x)
     y = np.zeros_like(x)
     lib().orc_wht_dense(_p(x, C.c_double), _p(y, C.c_double), C.c_uint64(x.size))
+    return y
+
+
+def wht_rows(x, idx):
+    """Entries idx of the unnormalised transform H x, each by the entry formula (O(n) per entry).  x must be
+    a contiguous fp64 array (it is not copied: it may be large)."""
+    assert x.dtype == np.float64 and x.flags["C_CONTIGUOUS"]
+    idx = np.ascontiguousarray(np.atleast_1d(idx), dtype=np.uint64)
+    y = np.zeros(idx.size, dtype=np.float64)
+    lib().orc_wht_rows(_p(x, C.c_double), C.c_uint64(x.size), _p(idx, C.c_uint64), C.c_uint64(idx.size),
+                       _p(y, C.c_double))
     return y
 
 

@@ -506,6 +506,21 @@ def test_block_range_equals_full(oracle):
     assert np.array_equal(decp, dec[64 * 5:64 * 9])
 
 
+def test_single_entries_of_the_transform_and_bulk_eps(oracle):
+    """The helpers behind the sampled checks of transforms too long to run whole: single entries of H x against
+    the Kronecker-built matrix, and the bulk eps draw against the per-coordinate one."""
+    k = 9
+    n = 1 << k
+    x = np.random.default_rng(12).standard_normal(n)
+    idx = np.array([0, 1, 2, 77, 255, 256, n - 1], dtype=np.uint64)
+    want = kron_hadamard(k) @ x
+    got = oracle.wht_rows(np.ascontiguousarray(x), idx)
+    assert np.allclose(got, want[idx.astype(int)], rtol=0, atol=1e-11)
+    e = oracle.eps_fill(11, 5, 3, 1000, 700)                     # straddles generator blocks of 128
+    assert np.array_equal(e, oracle.eps(11, 5, 3, np.arange(1000, 1700)))
+    assert set(np.unique(e)) == {-1.0, 1.0}
+
+
 def test_oracle_is_clean_under_host_sanitizers(tmp_path):
     """The oracle, driven through whole rounds on exactly sized arrays, under AddressSanitizer and
     UndefinedBehaviorSanitizer (host only): no out-of-bounds access, no undefined operation."""
