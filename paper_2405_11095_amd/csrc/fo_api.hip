@@ -358,6 +358,11 @@ int launch_pack_s(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigA
         return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, true, STATS>, grid, block, st, c, tab);
     }
     if (dither && c.S == 15) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 15, false, STATS>, grid, block, st, c, tab);
+    if constexpr (IN == IN_GRAD && !STATS) { // block lengths of the blocked workload, compiled for their stage count
+        if (dither && c.S == 10) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 10, false, false>, grid, block, st, c, tab);
+        if (dither && c.S == 12) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 12, false, false>, grid, block, st, c, tab);
+        if (dither && c.S == 14) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 14, false, false>, grid, block, st, c, tab);
+    }
     if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true, 0, false, STATS>, grid, block, st, c, tab);
     if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 0, false, STATS>, grid, block, st, c, tab);
     return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, false, STATS>, grid, block, st, c, tab);
@@ -529,7 +534,10 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     if (pl->npass == 0) {
         c.dst = out; c.len_out = len_out; c.store_mode = store_mode; c.out_coef = out_coef; c.delta = delta;
         if (multik) FO_TRY(launch(pl, KID_DEC_SINGLE, (k_contig<IN_BITS, OUT_F32, false, false, 0, true>), grid, block, st, c, none));
-        else FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile, grid, block, st, c));
+        else if (c.S == 10) FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile<10>, grid, block, st, c));
+        else if (c.S == 12) FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile<12>, grid, block, st, c));
+        else if (c.S == 14) FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile<14>, grid, block, st, c));
+        else FO_TRY(launch(pl, KID_DEC_SINGLE, k_decode_tile<0>, grid, block, st, c));
         return FO_OK;
     }
     if (pl->logb == 16 && !multik) {
@@ -641,7 +649,11 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         sa.enc.src = gbar;
         sa.bits_up = bits_up; sa.scales_up = scales_up; sa.M = M;
         sa.coef = 2.f * mean_coef; // the decode side carries half values
-        FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile, dim3((unsigned)pl->ntiles, 1), dim3(kThreads), st, sa));
+        const dim3 mgrid((unsigned)pl->ntiles, 1), mblock(kThreads);
+        if (pl->S == 10) FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<10>, mgrid, mblock, st, sa));
+        else if (pl->S == 12) FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<12>, mgrid, mblock, st, sa));
+        else if (pl->S == 14) FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<14>, mgrid, mblock, st, sa));
+        else FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<0>, mgrid, mblock, st, sa));
         return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
                              nullptr, 0, st);
     }

@@ -26,6 +26,8 @@ struct ServerTileArgs {
     float coef;               // value = lambda_n * coef * (half-valued integer): 2 / (sqrt(b) M)
 };
 
+// SC: compiled for transforms of 2^SC points (the block lengths of the blocked workload), 0: length read at run time.
+template <int SC>
 __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs sa)
 {
     // two sets of tables used in turn, so that the worker loop needs no barrier of its own
@@ -35,7 +37,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
     const ContigArgs &a = sa.enc;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x;
-    const uint32_t S = a.S;
+    const uint32_t S = SC ? (uint32_t)SC : a.S;
     uint32_t rk1, rlo;
     resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
     const uint64_t base = (uint64_t)tile << kTileLog2;
@@ -68,7 +70,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
         s16x2 v[32];
         uint32_t tl = t;
         asm volatile("" : "+v"(tl));
-        declow_tile<0>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, xbuf, v, tl);
+        declow_tile<SC>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, xbuf, v, tl);
         __syncthreads(); // the exchange buffer is read; the next worker's first exchange may write it
         // the table addresses are recomputed for every worker: hoisted out of the loop they would hold 64 registers
         // next to the 64 accumulators
@@ -100,6 +102,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
 // coordinates, stored / accumulated / applied as x -= delta * value (eq. "workers update").  Uses of the
 // argument block: src (packed signs), W, S, nblocks, scales (+ stride), eps_party0, the generator key,
 // dst, len_out, store_mode, out_coef (for half-valued integers), delta.
+template <int SC>
 __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
 {
     __shared__ uint32_t lds[kXWords + kEpsWords + kLamWords];
@@ -108,7 +111,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
     float *const lam = reinterpret_cast<float *>(lds + kXWords + kEpsWords);
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t tile = blockIdx.x, slot = blockIdx.y;
-    const uint32_t S = a.S;
+    const uint32_t S = SC ? (uint32_t)SC : a.S;
     uint32_t rk1, rlo;
     resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
     const uint64_t base = (uint64_t)tile << kTileLog2;
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
     }
     s16x2 v[32];
     const uint32_t *words = reinterpret_cast<const uint32_t *>(static_cast<const uint64_t *>(a.src) + slot * a.src_stride);
-    declow_tile<0>(words, a.W, tile, S, xbuf, xbuf, v); // its barriers publish the tables
+    declow_tile<SC>(words, a.W, tile, S, xbuf, xbuf, v); // its barriers publish the tables
 
     float2 *dst = reinterpret_cast<float2 *>(static_cast<float *>(a.dst) + base);
     const uint64_t room = a.len_out > base ? a.len_out - base : 0; // valid coordinates of this tile
