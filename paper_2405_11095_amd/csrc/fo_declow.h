@@ -37,7 +37,8 @@ constexpr uint32_t walsh_mask32(int j)
 
 // Decode-side stages of one tile from its 1024 packed 32-bit words, result in layout LC as 32 packed pairs.
 // SC = 15: all fifteen stages (transform length >= 2^15); SC = 0: the S = 6..15 stages of a blocked transform,
-// S read at run time (stage k runs iff k < S; the popcount stages b0..b4 always do); other SC: compiled for S = SC.  words points at the party's packed vector.
+// S read at run time (stage k runs iff k < S; the popcount stages b0..b4 always do); other SC: compiled for S = SC.
+// words points at the party's packed vector.
 // xa, xb: kXWords words of LDS each for the first (wave-private) and the second (workgroup-wide) exchange; they
 // may be the same buffer.  The second exchange starts with a barrier (all earlier reads of xb are over) and its
 // reads are not followed by one: a caller that loops must not write xb again before its next barrier, which a
