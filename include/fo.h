@@ -137,7 +137,10 @@ const char *fo_last_hip_error(void);
  * the plan's K for party FO_PARTY_SERVER (then bits is uint64[P][W], see "Averaged downlink quantiser").
  *   g       device fp32[len]: len = d for a worker, ntot when party == FO_PARTY_SERVER
  *   round   iteration t; party: worker id < M, or FO_PARTY_SERVER
- *   flags   0: scales[] is written with the amplitudes the rule gives;
+ *   flags   0: scales[] is written with the amplitudes the rule gives (a worker: alpha and the plan's scale
+ *           rule.  Party FO_PARTY_SERVER on its own knows no worker amplitudes, so Thm 5.5's server rule is
+ *           left to fo_server_aggregate; here it gets alpha_s sqrt(ln b / b) ||g_block|| under FO_SCALE_L2
+ *           and alpha B sqrt(ln b / b) under FO_SCALE_BOUND);
  *           FO_FORCE_SCALE: scales[] is read and used as given
  *   bits    device uint64[W] out;  scales device fp32[nblocks] in or out                      */
 int fo_encode(fo_plan *plan, const float *g, uint64_t round, uint32_t party, uint32_t flags,

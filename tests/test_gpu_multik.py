@@ -38,13 +38,13 @@ def test_round_trip_with_averaged_downlink(env, name, d, M, blk, K, kw):
     P.gates(rep)
 
 
-@pytest.mark.parametrize("d,blk,K", [(50_000, 0, 4), (9_000, 8, 6), (150_000, 16, 3)])
+@pytest.mark.parametrize("d,blk,K", [(50_000, 0, 4), (9_000, 8, 6), (150_000, 16, 3), (60_000, 0, 1), (3_000, 10, 1)])
 def test_server_party_encode_and_decode(env, d, blk, K):
     """fo_encode / fo_decode for the server party use the K-fold quantiser on their own as well."""
     import torch
     O, B, inputs, dev = env
-    plan = B.Plan(d=d, M=1, block_log2=blk, K=K, seed=77)
-    p = O.params(d=d, M=1, block_log2=blk, K=K, seed=77)
+    plan = B.Plan(d=d, M=1, block_log2=blk, K=K, seed=77, alpha=2.0, alpha_s=2.5)
+    p = O.params(d=d, M=1, block_log2=blk, K=K, seed=77, alpha=2.0, alpha_s=2.5)
     b, nb, nt = O.geometry(p)
     x = np.zeros(nt, dtype=np.float32)
     x[:d] = inputs.gaussian(d, 1)
@@ -59,6 +59,10 @@ def test_server_party_encode_and_decode(env, d, blk, K):
     q_gpu = P.planes_to_code(planes.cpu().numpy().view(np.uint64), nt, K)
     bad, exempt, raw = P.compare_codes(q_gpu, r["q"], r["margin"], h_lam, b)
     assert bad == 0, (bad, exempt, raw)
+    # the server party's own measured-norm amplitude carries alpha_s: the encoder's rule with that factor
+    p_s = O.params(d=d, M=1, block_log2=blk, K=K, seed=77, alpha=2.5, alpha_s=2.5)
+    free = O.encode(p_s, x[:d].astype(np.float64), 3, SERVER, K=K)["lam"]
+    assert np.max(np.abs(h_lam - free) / np.where(free > 0, free, 1.0)) <= 1e-6
     dec = O.decode(p, q_gpu, h_lam.astype(np.float64), 3, SERVER, K=K)[:d]
     assert P.rel_l2(out.cpu().numpy(), dec) <= 1e-5
     plan.close()
