@@ -130,6 +130,37 @@ def test_all_shared_eps_zero_transform_server(env, name, d, M, blk, K):
     gates(rep)
 
 
+@pytest.mark.parametrize("d,blk,eps_mode", [(20_000, 0, 0), (50_000, 0, 0), (300_000, 0, 0), (70_000, 10, 0),
+                                            (200_000, 16, 1), (5_000, 7, 2)])
+def test_worker_message_decode(env, d, blk, eps_mode):
+    """fo_decode of a worker's own message (the call a hand-rolled server would make): D_{eps_n,lambda_n}(q_n)
+    against the oracle's decoder, for a worker other than 0 (its own eps stream unless the mode shares it)."""
+    import torch
+    O, B, inputs, dev = env
+    M, m, rnd = 3, 2, 5
+    plan = B.Plan(d=d, M=M, block_log2=blk, seed=91, eps_mode=eps_mode)
+    p = O.params(d=d, M=M, block_log2=blk, seed=91, eps_mode=eps_mode)
+    b, nb, nt = O.geometry(p)
+    g = inputs.heavy_tailed(d, m)
+    bits = torch.zeros(plan.W, dtype=torch.int64, device=dev)
+    lam = torch.zeros(nb, dtype=torch.float32, device=dev)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan.fo_encode(torch.from_numpy(g).to(dev), rnd, m, bits, lam)
+    plan.fo_decode(bits, lam, rnd, m, out)
+    torch.cuda.synchronize()
+    h_lam = lam.cpu().numpy().astype(np.float64)
+    q = O.unpack(bits.cpu().numpy().view(np.uint64), nt)      # +-1
+    dec = O.decode(p, q, h_lam, rnd, m)[:d]
+    from tests.parity import rel_l2
+    assert rel_l2(out.cpu().numpy(), dec) <= 1e-5
+    # and the round trip is the paper's estimator: norm lambda sqrt(b) per block (every entry of q is +-1)
+    full = np.zeros(nt)
+    full[:d] = out.cpu().numpy()
+    if d == nt:
+        assert np.allclose(np.linalg.norm(full.reshape(nb, b), axis=1), h_lam * np.sqrt(b), rtol=1e-5)
+    plan.close()
+
+
 def test_forced_scale_is_used(env):
     import torch
     O, B, inputs, dev = env
