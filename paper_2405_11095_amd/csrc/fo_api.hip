@@ -358,10 +358,27 @@ int launch_pack_s(fo_plan *pl, int kid, dim3 grid, hipStream_t st, const ContigA
         return launch(pl, kid, k_contig<IN, OUT_PACK, false, false, 0, true, STATS>, grid, block, st, c, tab);
     }
     if (dither && c.S == 15) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 15, false, STATS>, grid, block, st, c, tab);
-    if constexpr (IN == IN_GRAD && !STATS) { // block lengths of the blocked workload, compiled for their stage count
-        if (dither && c.S == 10) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 10, false, false>, grid, block, st, c, tab);
-        if (dither && c.S == 12) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 12, false, false>, grid, block, st, c, tab);
-        if (dither && c.S == 14) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 14, false, false>, grid, block, st, c, tab);
+    if constexpr (IN == IN_GRAD && !STATS) {
+        // block lengths of the blocked workload, compiled for their stage count; tiles that lie inside the input
+        // whole go to a variant without the per-chunk end-of-input checks
+        if (dither && (c.S == 10 || c.S == 12 || c.S == 14)) {
+            const uint64_t full64 = c.len_in >> kTileLog2;
+            const uint32_t nfull = (uint32_t)(full64 < grid.x ? full64 : grid.x);
+            ContigArgs cc = c;
+            auto go = [&](auto sc, auto guarded, uint32_t tile0, uint32_t ntile) -> int {
+                cc.tile0 = tile0;
+                return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, decltype(sc)::value, false, false, decltype(guarded)::value>,
+                              dim3(ntile, grid.y), block, st, cc, tab);
+            };
+            auto both = [&](auto sc) -> int {
+                if (nfull) FO_TRY(go(sc, std::false_type{}, 0u, nfull));
+                if (nfull < grid.x) FO_TRY(go(sc, std::true_type{}, nfull, grid.x - nfull));
+                return FO_OK;
+            };
+            if (c.S == 10) return both(std::integral_constant<int, 10>{});
+            if (c.S == 12) return both(std::integral_constant<int, 12>{});
+            return both(std::integral_constant<int, 14>{});
+        }
     }
     if (dither && small) return launch(pl, kid, k_contig<IN, OUT_PACK, true, true, 0, false, STATS>, grid, block, st, c, tab);
     if (dither) return launch(pl, kid, k_contig<IN, OUT_PACK, true, false, 0, false, STATS>, grid, block, st, c, tab);
@@ -384,7 +401,18 @@ int launch_pair(fo_plan *pl, dim3 grid, hipStream_t st, const ContigArgs &c, con
         if (dither) return launch(pl, KID_ENC_PAIR, k_contig_pair<true, true>, grid, block, st, c, tab);
         return launch(pl, KID_ENC_PAIR, k_contig_pair<false, true>, grid, block, st, c, tab);
     }
-    if (dither) return launch(pl, KID_ENC_PAIR, k_contig_pair<true, false>, grid, block, st, c, tab);
+    if (dither) {
+        // blocks that lie inside the input whole: no per-chunk end-of-input checks
+        const uint64_t full64 = c.len_in >> 16;
+        const uint32_t nfull = (uint32_t)(full64 < grid.x ? full64 : grid.x);
+        ContigArgs cc = c;
+        if (nfull) FO_TRY(launch(pl, KID_ENC_PAIR, k_contig_pair<true, false, false>, dim3(nfull, grid.y), block, st, cc, tab));
+        if (nfull < grid.x) {
+            cc.tile0 = 2u * nfull;
+            FO_TRY(launch(pl, KID_ENC_PAIR, k_contig_pair<true, false, true>, dim3(grid.x - nfull, grid.y), block, st, cc, tab));
+        }
+        return FO_OK;
+    }
     return launch(pl, KID_ENC_PAIR, k_contig_pair<false, false>, grid, block, st, c, tab);
 }
 

@@ -54,6 +54,7 @@ struct ContigArgs {
     uint32_t K;             // MULTIK: averaging count of the quantiser (Def. 3.2) being applied / decoded
     uint32_t planes;        // MULTIK: bit planes of the message, ceil(log2(K + 1)); plane p starts at word p * W
     uint32_t scales_only;   // IN_GRAD: write the blocks' amplitudes and stop (no transform)
+    uint32_t tile0;         // first tile of this launch (a launch may cover a range of tiles)
     uint32_t party0;        // party id of slot 0 (slot y is party0 + y); FO_PARTY_SERVER stays as is
     uint32_t eps_party0;    // same for the eps stream
     uint32_t k0, k1, round_lo;
@@ -83,7 +84,7 @@ struct ContigArgs {
 // swap their values through LDS, the lower forms x_lo + x_hi and the upper x_lo - x_hi, and each runs the fifteen
 // remaining stages on its own tile as usual.  The 2^16-point transform then costs one pass over memory instead
 // of two.  The block's norm is the sum of the two groups' partial sums.
-template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK, bool STATS = false, bool PAIR = false>
+template <int IN, int OUT, bool DITHER, bool SMALLB, int SC, bool MULTIK, bool STATS = false, bool PAIR = false, bool GUARDED = true>
 __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &tab, const uint32_t tile, const uint32_t slot,
                                             uint32_t *const lds, const uint32_t t, uint32_t *const lds_partner = nullptr)
 {
@@ -113,7 +114,8 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
     if constexpr (IN == IN_GRAD || IN == IN_F32) {
         const float *src = (IN == IN_GRAD && a.use_tab) ? tab.p[slot]
                                                         : static_cast<const float *>(a.src) + slot * a.src_stride;
-        const uint64_t limit = (IN == IN_GRAD) ? a.len_in : ~0ull;
+        // GUARDED = false: the caller vouches that the whole tile lies inside the input (no per-chunk checks)
+        const uint64_t limit = (IN == IN_GRAD && GUARDED) ? a.len_in : ~0ull;
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
             const uint64_t i = base + wave * 4096u + c * 256u + lane * 4u;
@@ -542,20 +544,21 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
     }
 }
 
-template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false, bool STATS = false>
+template <int IN, int OUT, bool DITHER = false, bool SMALLB = false, int SC = 0, bool MULTIK = false, bool STATS = false,
+          bool GUARDED = true>
 __global__ __launch_bounds__(kThreads, 4) void k_contig(const ContigArgs a, const PtrTab tab)
 {
     __shared__ uint32_t lds[kLdsWords];
-    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK, STATS>(a, tab, blockIdx.x, blockIdx.y, lds, threadIdx.x);
+    contig_tile<IN, OUT, DITHER, SMALLB, SC, MULTIK, STATS, false, GUARDED>(a, tab, a.tile0 + blockIdx.x, blockIdx.y, lds, threadIdx.x);
 }
 
 // Encode of blocks of exactly 2^16 coordinates in one pass: 1024 threads, one block (two tiles) per workgroup.
-template <bool DITHER, bool MULTIK>
+template <bool DITHER, bool MULTIK, bool GUARDED = true>
 __global__ __launch_bounds__(2 * kThreads) void k_contig_pair(const ContigArgs a, const PtrTab tab)
 {
     __shared__ uint32_t lds[2 * kLdsWords];
     const uint32_t h = threadIdx.x >> 9;
-    contig_tile<IN_GRAD, OUT_PACK, DITHER, false, 15, MULTIK, false, true>(a, tab, 2u * blockIdx.x + h, blockIdx.y, lds + h * kLdsWords,
+    contig_tile<IN_GRAD, OUT_PACK, DITHER, false, 15, MULTIK, false, true, GUARDED>(a, tab, a.tile0 + 2u * blockIdx.x + h, blockIdx.y, lds + h * kLdsWords,
                                                                            threadIdx.x & 511u, lds + (h ^ 1u) * kLdsWords);
 }
 
