@@ -24,7 +24,77 @@ def _encode(B, torch, dev, plan, g, rnd, party, flags=0, scales=None):
     return bits, lam
 
 
-@pytest.mark.parametrize("d,blk", [(1000, 0), (70_000, 0), (5000, 7)])
+@pytest.mark.parametrize("d,blk", [(1 << 15, 0), (1 << 16, 0), (3 << 16, 16), (1 << 18, 0), (1 << 14, 10), (1000, 6)])
+def test_decode_of_walsh_rows_is_a_spike(env, d, blk):
+    """A message that is row j of the Walsh matrix decodes to lambda sqrt(b) eps_j e_j: the largest value an inverse
+    transform can produce (all b signs add up), elsewhere exact zeros.  j = 0 is the all-ones message.  Exercises
+    the integer decode paths at the end of their range (2^14, 2^15 and 2^16 in half values) and their offsets."""
+    import torch
+    O, B, inputs, dev = env
+    plan = B.Plan(d=d, M=2, block_log2=blk, seed=19)
+    p = O.params(d=d, M=2, block_log2=blk, seed=19)
+    b, nb, nt = O.geometry(p)
+    lam = np.linspace(1.0, 2.0, nb).astype(np.float32)
+    i = np.arange(b, dtype=np.uint64)
+    rs = np.random.default_rng(5)
+    for j in [0, 1, 31, 32, 33, b // 2, b - 1, int(rs.integers(0, b)), int(rs.integers(0, b))]:
+        par = np.zeros(b, dtype=np.uint64)
+        x = i & np.uint64(j)
+        for sh in (32, 16, 8, 4, 2, 1):                        # parity of popcount(i & j)
+            x ^= x >> np.uint64(sh)
+        q_blk = 1 - 2 * (x & np.uint64(1)).astype(np.int32)    # (-1)^popcount(i & j)
+        q = np.tile(q_blk, nb)
+        bits = O.pack(q)
+        for party in (1, SERVER):
+            out = torch.zeros(d, dtype=torch.float32, device=dev)
+            plan.fo_decode(torch.from_numpy(bits.view(np.int64)).to(dev), torch.from_numpy(lam).to(dev), 4, party, out)
+            torch.cuda.synchronize()
+            want = O.decode(p, q, lam.astype(np.float64), 4, party)[:d]
+            got = out.cpu().numpy().astype(np.float64)
+            spikes = np.arange(nb) * b + j
+            spikes = spikes[spikes < d]
+            assert np.count_nonzero(want) == spikes.size and np.all(np.abs(want[spikes]) > 0)
+            assert np.array_equal(got != 0, want != 0), (j, party)
+            assert np.allclose(got[spikes], want[spikes], rtol=1e-6, atol=0), (j, party)
+    plan.close()
+
+
+def test_extreme_messages_long_transform(env):
+    """n = 2^25, both workers send the all-ones message: the inverse transform's value at coordinate 0 is n, the
+    largest integer the fp32 stages of the server pass and of the last decode pass ever hold (2^24 in half values,
+    still exact).  Mean, downlink bits and decode against the oracle."""
+    import torch
+    O, B, inputs, dev = env
+    d, M, rnd = 1 << 25, 2, 6
+    plan = B.Plan(d=d, M=M, seed=23)
+    p = O.params(d=d, M=M, seed=23)
+    b, nb, nt = O.geometry(p)
+    W = nt // 64
+    bits_up = torch.full((M, W), -1, dtype=torch.int64, device=dev)
+    lam_up = torch.tensor([[1.0], [0.5]], dtype=torch.float32, device=dev)
+    bits_down = torch.zeros(W, dtype=torch.int64, device=dev)
+    lam_s = torch.zeros(nb, dtype=torch.float32, device=dev)
+    gbar = torch.zeros(nt, dtype=torch.float32, device=dev)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan.fo_server_aggregate(bits_up, lam_up, rnd, bits_down, lam_s, gbar)
+    plan.fo_decode(bits_up[1], lam_up[1], rnd, 1, out)
+    torch.cuda.synchronize()
+    h_up = bits_up.cpu().numpy().view(np.uint64)
+    s = O.server(p, h_up, lam_up.cpu().numpy().astype(np.float64), rnd, lam_s=lam_s.cpu().numpy().astype(np.float64),
+                 want_margin=True)
+    h_gbar = gbar.cpu().numpy().astype(np.float64)
+    assert np.count_nonzero(s["gbar"]) == 1 and np.count_nonzero(h_gbar) == 1
+    assert abs(h_gbar[0] - s["gbar"][0]) <= 1e-6 * abs(s["gbar"][0])
+    from tests.parity import compare_bits
+    bad, exempt, raw = compare_bits(bits_down.cpu().numpy().view(np.uint64), s["margin"], lam_s.cpu().numpy(), b)
+    assert bad == 0, (bad, exempt, raw)
+    dec = O.decode(p, O.unpack(h_up[1], nt), lam_up[1].cpu().numpy().astype(np.float64), rnd, 1)[:d]
+    h_out = out.cpu().numpy().astype(np.float64)
+    assert np.count_nonzero(h_out) == 1 and abs(h_out[0] - dec[0]) <= 1e-6 * abs(dec[0])
+    plan.close()
+
+
+@pytest.mark.parametrize("d,blk", [(1000, 0), (70_000, 0), (5000, 7), (50_000, 0), (200_000, 16)])
 def test_zero_gradient(env, d, blk):
     """sign(0) = +1: every bit is set, lambda = 0, the decoded vector and the update are exactly 0."""
     import torch
@@ -79,14 +149,17 @@ def test_determinism_and_seed_sensitivity(env):
         assert 0.3 < frac < 0.7
 
 
-def test_repeat_encodes_agree_large(env):
+@pytest.mark.parametrize("blk", [0, 12, 16])
+def test_repeat_encodes_agree_large(env, blk):
     """Ten encodes of one 2^22-coordinate vector give the same 65536 words every time (the packed words
-    travel through scalar registers and lane writes, where a missed wait state shows up as rare stale words)."""
+    travel through scalar registers and lane writes, where a missed wait state shows up as rare stale words).
+    Block lengths: one long transform, single-tile blocks, and blocks of two tiles (two groups of a workgroup
+    that must agree on the amplitude to the bit)."""
     import torch
     O, B, inputs, dev = env
     d = 1 << 22
     g = inputs.gaussian(d, 3)
-    plan = B.Plan(d=d, M=1, seed=11)
+    plan = B.Plan(d=d, M=1, seed=11, block_log2=blk)
     ref, lref = _encode(B, torch, dev, plan, g, 9, 0)
     for _ in range(9):
         b, l = _encode(B, torch, dev, plan, g, 9, 0)
