@@ -59,19 +59,21 @@ def test_decode_of_walsh_rows_is_a_spike(env, d, blk):
     plan.close()
 
 
-def test_extreme_messages_long_transform(env):
-    """n = 2^25, both workers send the all-ones message: the inverse transform's value at coordinate 0 is n, the
-    largest integer the fp32 stages of the server pass and of the last decode pass ever hold (2^24 in half values,
-    still exact).  Mean, downlink bits and decode against the oracle."""
+@pytest.mark.parametrize("d,blk", [(1 << 25, 0), (1 << 17, 15), (1 << 16, 12), (1 << 18, 16)])
+def test_extreme_messages_through_the_server(env, d, blk):
+    """Both workers send the all-ones message: the inverse transform's value at the first coordinate of a block is
+    b, the largest integer the decode side ever holds (for n = 2^25: 2^24 in half values in the fp32 stages of the
+    server pass, still exact).  Mean, downlink bits and one worker decode against the oracle, for the two-pass
+    server, the single-tile mean kernel and blocks of two tiles."""
     import torch
     O, B, inputs, dev = env
-    d, M, rnd = 1 << 25, 2, 6
-    plan = B.Plan(d=d, M=M, seed=23)
-    p = O.params(d=d, M=M, seed=23)
+    M, rnd = 2, 6
+    plan = B.Plan(d=d, M=M, block_log2=blk, seed=23)
+    p = O.params(d=d, M=M, block_log2=blk, seed=23)
     b, nb, nt = O.geometry(p)
     W = nt // 64
     bits_up = torch.full((M, W), -1, dtype=torch.int64, device=dev)
-    lam_up = torch.tensor([[1.0], [0.5]], dtype=torch.float32, device=dev)
+    lam_up = torch.tensor([[1.0] * nb, [0.5] * nb], dtype=torch.float32, device=dev)
     bits_down = torch.zeros(W, dtype=torch.int64, device=dev)
     lam_s = torch.zeros(nb, dtype=torch.float32, device=dev)
     gbar = torch.zeros(nt, dtype=torch.float32, device=dev)
@@ -83,14 +85,15 @@ def test_extreme_messages_long_transform(env):
     s = O.server(p, h_up, lam_up.cpu().numpy().astype(np.float64), rnd, lam_s=lam_s.cpu().numpy().astype(np.float64),
                  want_margin=True)
     h_gbar = gbar.cpu().numpy().astype(np.float64)
-    assert np.count_nonzero(s["gbar"]) == 1 and np.count_nonzero(h_gbar) == 1
-    assert abs(h_gbar[0] - s["gbar"][0]) <= 1e-6 * abs(s["gbar"][0])
+    first = np.arange(nb) * b
+    assert np.count_nonzero(s["gbar"]) == nb and np.count_nonzero(h_gbar) == nb
+    assert np.all(np.abs(h_gbar[first] - s["gbar"][first]) <= 1e-6 * np.abs(s["gbar"][first]))
     from tests.parity import compare_bits
     bad, exempt, raw = compare_bits(bits_down.cpu().numpy().view(np.uint64), s["margin"], lam_s.cpu().numpy(), b)
     assert bad == 0, (bad, exempt, raw)
     dec = O.decode(p, O.unpack(h_up[1], nt), lam_up[1].cpu().numpy().astype(np.float64), rnd, 1)[:d]
     h_out = out.cpu().numpy().astype(np.float64)
-    assert np.count_nonzero(h_out) == 1 and abs(h_out[0] - dec[0]) <= 1e-6 * abs(dec[0])
+    assert np.count_nonzero(h_out) == nb and np.all(np.abs(h_out[first] - dec[first]) <= 1e-6 * np.abs(dec[first]))
     plan.close()
 
 
