@@ -152,6 +152,22 @@ def test_determinism_and_seed_sensitivity(env):
         assert 0.3 < frac < 0.7
 
 
+@pytest.mark.parametrize("d,blk", [(100_000, 0), (40_000, 0), (300_000, 12), (200_000, 16)])
+def test_scaling_by_a_power_of_two_changes_only_the_amplitude(env, d, blk):
+    """The codec is homogeneous: g -> 2^k g scales every fp32 intermediate exactly, so the message is the same bit
+    for bit and the amplitude is 2^k times the old one (k = +-40: well inside the fp32 range of the norms)."""
+    import torch
+    O, B, inputs, dev = env
+    g = inputs.gaussian(d, 4)
+    plan = B.Plan(d=d, M=1, block_log2=blk, seed=29)
+    ref, lref = _encode(B, torch, dev, plan, g, 2, 0)
+    for k in (-40, 40):
+        b, l = _encode(B, torch, dev, plan, np.ldexp(g, k).astype(np.float32), 2, 0)
+        assert torch.equal(b, ref)
+        assert torch.equal(l, torch.ldexp(lref, torch.tensor(k, device=dev)))
+    plan.close()
+
+
 @pytest.mark.parametrize("blk", [0, 12, 16])
 def test_repeat_encodes_agree_large(env, blk):
     """Ten encodes of one 2^22-coordinate vector give the same 65536 words every time (the packed words
