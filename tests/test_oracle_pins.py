@@ -506,6 +506,20 @@ def test_block_range_equals_full(oracle):
     assert np.array_equal(decp, dec[64 * 5:64 * 9])
 
 
+def test_encoder_is_homogeneous(oracle):
+    """E(c x) = E(x) with amplitude c lambda for c > 0 (the rule lambda = alpha ||x|| sqrt(ln n / n) scales with x and
+    the quantiser only looks at signs of z + lambda u): exact for c a power of two, where no rounding changes."""
+    d = 3000
+    x = np.random.default_rng(21).standard_normal(d)
+    for blk in (0, 8):
+        p = oracle.params(d=d, seed=8, block_log2=blk)
+        ref = oracle.encode(p, x, 3, 1)
+        for k in (-20, 7):
+            r = oracle.encode(p, np.ldexp(x, k), 3, 1)
+            assert np.array_equal(r["bits"], ref["bits"])
+            assert np.array_equal(r["lam"], np.ldexp(ref["lam"], k))
+
+
 def test_single_entries_of_the_transform_and_bulk_eps(oracle):
     """The helpers behind the sampled checks of transforms too long to run whole: single entries of H x against
     the Kronecker-built matrix, and the bulk eps draw against the per-coordinate one."""
