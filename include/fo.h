@@ -83,6 +83,7 @@ extern "C" {
 #define FO_EALIGN (-2) /* a device pointer is not aligned as required                      */
 #define FO_EHIP (-3)   /* a HIP runtime call failed; see fo_last_hip_error              */
 #define FO_ENOMEM (-4) /* plan creation could not allocate its scratch memory         */
+#define FO_ESIZE (-5)  /* fo_encode_noalloc: vector longer than its static scratch takes  */
 
 #define FO_DITHER_UNIFORM 0u /* tau ~ U[-lambda, lambda], Def. 3.2                       */
 #define FO_DITHER_NONE 1u    /* tau = 0: plain sign of the flattened vector (ablation)   */
@@ -99,6 +100,7 @@ extern "C" {
 #define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */
 
 #define FO_MAX_WORKERS 64u
+#define FO_NOALLOC_MAX_N (1u << 22) /* largest padded length fo_encode_noalloc takes */
 #define FO_MAX_K 255u
 
 typedef struct {
@@ -162,6 +164,19 @@ int fo_decode(fo_plan *plan, const uint64_t *bits, const float *scales, uint64_t
 int fo_server_aggregate(fo_plan *plan, const uint64_t *bits_up, const float *scales_up,
                         uint64_t round, uint64_t *bits_down, float *scales_down,
                         float *gbar_or_null, void *hip_stream);
+
+/* fo_encode for callers that cannot allocate device memory: code running under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No plan: the geometry is derived from *params (host) at every call,
+ * and the intermediates of transforms longer than 2^15 points (an fp32 vector of the padded length and one sum
+ * of squares per tile) live in a static device array of 4 * FO_NOALLOC_MAX_N bytes + 512 bytes (16 MiB) that every
+ * device the library runs on holds until the process ends.  The call allocates and frees nothing, on the host or
+ * on the device, and enqueues kernels only.  Arguments, messages and amplitudes are those of fo_encode with a plan
+ * made from the same parameters (bit for bit); diagnostic counters and per-kernel timing are not available.
+ *   FO_ESIZE   the padded length exceeds FO_NOALLOC_MAX_N (fo_last_hip_error gives the figures)
+ * All calls on one device share that device's array, which keeps the last call's contents (every call overwrites
+ * what it reads, so nothing needs clearing): calls that overlap on one device, on whatever streams, race. */
+int fo_encode_noalloc(const fo_params *params, const float *g, uint64_t round, uint32_t party, uint32_t flags,
+                      uint64_t *bits, float *scales, void *hip_stream);
 
 /* One whole iteration (Sec. 4, "At iteration t"): M encodes, server, one downlink decode and
  * x <- x - delta * g^d (eq. "workers update").  Gives the same bits and the same x as the three

@@ -13,7 +13,7 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libfo.so")
 
-OK, EINVAL, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4
+OK, EINVAL, EALIGN, EHIP, ENOMEM, ESIZE = 0, -1, -2, -3, -4, -5
 DITHER_UNIFORM, DITHER_NONE = 0, 1
 SCALE_BOUND, SCALE_L2 = 0, 1
 EPS_INDEPENDENT, EPS_SHARED_WORKERS, EPS_SHARED_ALL = 0, 1, 2
@@ -21,17 +21,18 @@ SERVER_SCALE_THM, SERVER_SCALE_L2 = 0, 1
 PARTY_SERVER = 0xFFFFFFFF
 FORCE_SCALE = 1
 MAX_WORKERS = 64
+NOALLOC_MAX_N = 1 << 22
 
 EXPORTS = ("fo_plan_create", "fo_plan_destroy", "fo_padded_len", "fo_packed_words", "fo_num_scales",
            "fo_block_len", "fo_downlink_planes", "fo_scratch_bytes", "fo_last_hip_error", "fo_encode", "fo_decode",
-           "fo_server_aggregate", "fo_step", "fo_step_dev_round", "fo_step_messages", "fo_set_stats", "fo_profile_begin", "fo_profile_begin_kernel", "fo_profile_end")
+           "fo_server_aggregate", "fo_step", "fo_encode_noalloc", "fo_step_dev_round", "fo_step_messages", "fo_set_stats", "fo_profile_begin", "fo_profile_begin_kernel", "fo_profile_end")
 
 
 class FoError(RuntimeError):
     def __init__(self, code, where):
-        names = {EINVAL: "FO_EINVAL", EALIGN: "FO_EALIGN", EHIP: "FO_EHIP", ENOMEM: "FO_ENOMEM"}
+        names = {EINVAL: "FO_EINVAL", EALIGN: "FO_EALIGN", EHIP: "FO_EHIP", ENOMEM: "FO_ENOMEM", ESIZE: "FO_ESIZE"}
         detail = ""
-        if code == EHIP:
+        if code in (EHIP, ESIZE):
             detail = ": " + load_library().fo_last_hip_error().decode()
         super().__init__(f"{where} failed with {names.get(code, code)}{detail}")
         self.code = code
@@ -70,6 +71,7 @@ def load_library():
         lib.fo_last_hip_error.restype = C.c_char_p
         lib.fo_encode.argtypes = [vp, vp, u64, u32, u32, vp, vp, vp]
         lib.fo_decode.argtypes = [vp, vp, vp, u64, u32, vp, vp]
+        lib.fo_encode_noalloc.argtypes = [C.POINTER(Params), vp, u64, u32, u32, vp, vp, vp]
         lib.fo_server_aggregate.argtypes = [vp, vp, vp, u64, vp, vp, vp, vp]
         lib.fo_step.argtypes = [vp, C.POINTER(vp), vp, C.c_float, u64, vp]
         lib.fo_step_dev_round.argtypes = [vp, C.POINTER(vp), vp, C.c_float, vp, vp]
@@ -96,6 +98,14 @@ def _stream(stream):
         return stream
     import torch
     return torch.cuda.current_stream().cuda_stream
+
+
+def fo_encode_noalloc(params, g, rnd, party, bits, scales, flags=0, stream=None):
+    """fo_encode without a plan and without any allocation (static device scratch); params is a Params."""
+    rc = load_library().fo_encode_noalloc(C.byref(params), _ptr(g), rnd, party, flags, _ptr(bits), _ptr(scales),
+                                          _stream(stream))
+    if rc:
+        raise FoError(rc, "fo_encode_noalloc")
 
 
 class Plan:

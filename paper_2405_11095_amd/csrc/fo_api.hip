@@ -118,7 +118,7 @@ struct Profiler {
     bool on = false;
     static constexpr int kMax = 8192;
     hipEvent_t *ev = nullptr; // 2 * kMax events
-    int kid[kMax];
+    int *kid = nullptr;       // kMax entries, allocated with the events
     int used = 0;
     int only = -1; // >= 0: bracket launches of this kernel only
 };
@@ -157,11 +157,11 @@ struct fo_plan {
 
 extern "C" const char *fo_last_hip_error(void) { return g_hip_err; }
 
-extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
+namespace {
+
+// Validates the parameters and fills in everything of a plan that is host arithmetic (no device memory).
+int plan_geometry(const fo_params &q, fo_plan *pl)
 {
-    if (!params || !out) return FO_EINVAL;
-    *out = nullptr;
-    const fo_params &q = *params;
     if (q.d < 1 || q.M < 1 || q.M > FO_MAX_WORKERS) return FO_EINVAL;
     if (q.block_log2 != 0 && (q.block_log2 < 6 || q.block_log2 > 30)) return FO_EINVAL;
     if (q.K < 1 || q.K > FO_MAX_K) return FO_EINVAL;
@@ -173,15 +173,13 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
     if (q.server_scale != FO_SERVER_SCALE_THM && q.server_scale != FO_SERVER_SCALE_L2) return FO_EINVAL;
 
-    fo_plan *pl = new (std::nothrow) fo_plan();
-    if (!pl) return FO_ENOMEM;
     pl->p = q;
     pl->stats = nullptr;
     pl->round_dev = nullptr;
     if (q.block_log2 == 0) {
         uint32_t k = 6;
         while (((uint64_t)1 << k) < q.d) ++k;
-        if (k > 30) { delete pl; return FO_EINVAL; }
+        if (k > 30) return FO_EINVAL;
         pl->logb = k;
         pl->nblocks = 1;
     } else {
@@ -190,7 +188,7 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     }
     pl->b = (uint64_t)1 << pl->logb;
     pl->ntot = pl->b * pl->nblocks;
-    if (pl->ntot > ((uint64_t)1 << 32)) { delete pl; return FO_EINVAL; }
+    if (pl->ntot > ((uint64_t)1 << 32)) return FO_EINVAL;
     pl->W = pl->ntot / 64;
     pl->ntiles = (pl->ntot + kTile - 1) / kTile;
     pl->S = pl->logb < (uint32_t)kTileLog2 ? pl->logb : (uint32_t)kTileLog2;
@@ -198,17 +196,33 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
     pl->npass = high == 0 ? 0 : (high <= 10 ? 1 : 2);
     pl->hb[0] = pl->npass == 2 ? (high + 1) / 2 : high;
     pl->hb[1] = high - pl->hb[0];
-    if (q.eps_mode != FO_EPS_INDEPENDENT && pl->npass == 2) { delete pl; return FO_EINVAL; } // shared eps: not built for b > 2^25
+    if (q.eps_mode != FO_EPS_INDEPENDENT && pl->npass == 2) return FO_EINVAL; // shared eps: not built for b > 2^25
     pl->planes = 0;
     while ((q.K >> pl->planes) != 0) ++pl->planes;
     // the decode side carries K b / 2 at most in int32 between its passes
-    if (q.K > 1 && pl->npass > 0 && (uint64_t)q.K * (pl->b / 2) >= ((uint64_t)1 << 31)) { delete pl; return FO_EINVAL; }
+    if (q.K > 1 && pl->npass > 0 && (uint64_t)q.K * (pl->b / 2) >= ((uint64_t)1 << 31)) return FO_EINVAL;
     const double bd = (double)pl->b;
     pl->coef_lambda = (float)((double)q.alpha * std::sqrt(std::log(bd) / bd));
     pl->sqrtb = (float)std::sqrt(bd);
     pl->rsqrtb = (float)(1.0 / std::sqrt(bd));
     pl->coef_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd)));
     pl->coef_lambda_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd) / bd));
+    return FO_OK;
+}
+
+} // namespace
+
+extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
+{
+    if (!params || !out) return FO_EINVAL;
+    *out = nullptr;
+    const fo_params &q = *params;
+    fo_plan *pl = new (std::nothrow) fo_plan();
+    if (!pl) return FO_ENOMEM;
+    {
+        const int rc = plan_geometry(q, pl);
+        if (rc) { delete pl; return rc; }
+    }
 
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t sz_a = pl->npass ? up((size_t)q.M * pl->ntot * 4) : 0;
@@ -248,6 +262,7 @@ extern "C" void fo_plan_destroy(fo_plan *plan)
     if (plan->prof.ev) {
         for (int i = 0; i < 2 * Profiler::kMax; ++i) (void)hipEventDestroy(plan->prof.ev[i]);
         delete[] plan->prof.ev;
+        delete[] plan->prof.kid;
     }
     delete plan;
 }
@@ -844,7 +859,8 @@ extern "C" int fo_profile_begin(fo_plan *pl)
     Profiler &pf = pl->prof;
     if (!pf.ev) {
         pf.ev = new (std::nothrow) hipEvent_t[2 * Profiler::kMax];
-        if (!pf.ev) return FO_ENOMEM;
+        pf.kid = new (std::nothrow) int[Profiler::kMax];
+        if (!pf.ev || !pf.kid) return FO_ENOMEM;
         for (int i = 0; i < 2 * Profiler::kMax; ++i)
             if (!hip_ok(hipEventCreate(&pf.ev[i]), "hipEventCreate")) return FO_EHIP;
     }
@@ -892,4 +908,88 @@ extern "C" int fo_profile_end(fo_plan *pl, fo_kernel_time *out, size_t cap, size
     }
     *count = n;
     return FO_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Encode without any allocation: intermediates in a static device array
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr uint64_t kNoallocMaxN = (uint64_t)FO_NOALLOC_MAX_N;
+constexpr uint64_t kNoallocPartials = kNoallocMaxN >> kTileLog2;          // one sum of squares per tile
+constexpr uint64_t kNoallocWords = kNoallocMaxN + ((kNoallocPartials + 63) & ~(uint64_t)63);
+
+} // namespace
+
+// fp32 intermediate of the two-pass encode [FO_NOALLOC_MAX_N], then the tile sums of squares.  Every device the
+// library runs on holds its own copy until the process ends.  Host code never uses this name as an address: the
+// per-device address comes from hipGetSymbolAddress (noalloc_scratch below).
+static __device__ __align__(256) float scratch[kNoallocWords];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+float *g_scratch_ptr[kMaxDevices]; // device address of `scratch` on each device, set by the first call there
+
+int noalloc_scratch(float **out)
+{
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev), "hipGetDevice")) return FO_EHIP;
+    if (dev < 0 || dev >= kMaxDevices) {
+        std::snprintf(g_hip_err, sizeof(g_hip_err), "fo_encode_noalloc: device ordinal %d not supported", dev);
+        return FO_EHIP;
+    }
+    float *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void *sym = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)")) return FO_EHIP;
+        if (!sym) {
+            std::snprintf(g_hip_err, sizeof(g_hip_err), "fo_encode_noalloc: no address for the static scratch array");
+            return FO_EHIP;
+        }
+        p = static_cast<float *>(sym);
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE); // every thread would store the same value
+    }
+    *out = p;
+    return FO_OK;
+}
+
+} // namespace
+
+extern "C" int fo_encode_noalloc(const fo_params *params, const float *g, uint64_t round, uint32_t party, uint32_t flags,
+                                 uint64_t *bits, float *scales, void *hip_stream)
+{
+    if (!params || !g || !bits || !scales) return FO_EINVAL;
+    fo_plan pl; // host object on the stack: geometry only, no device memory of its own
+    {
+        const int rc = plan_geometry(*params, &pl);
+        if (rc) return rc;
+    }
+    if (pl.ntot > kNoallocMaxN) {
+        std::snprintf(g_hip_err, sizeof(g_hip_err), "fo_encode_noalloc: padded length %llu exceeds FO_NOALLOC_MAX_N = %llu",
+                      (unsigned long long)pl.ntot, (unsigned long long)kNoallocMaxN);
+        return FO_ESIZE;
+    }
+    if (party != FO_PARTY_SERVER && party >= pl.p.M) return FO_EINVAL;
+    if (flags & ~FO_FORCE_SCALE) return FO_EINVAL;
+    if (!aligned(g, 16) || !aligned(bits, 8) || !aligned(scales, 4)) return FO_EALIGN;
+    float *ptr = nullptr;
+    {
+        const int rc = noalloc_scratch(&ptr);
+        if (rc) return rc;
+    }
+    pl.scratch = nullptr;
+    pl.scratch_bytes = 0;
+    pl.buf_a = ptr;                 // fp32 intermediate between the strided and the contiguous pass
+    pl.buf_b = pl.buf_c = nullptr;  // transforms of up to 2^22 points never take a third pass
+    pl.partials = ptr + kNoallocMaxN;
+    pl.bits_up = pl.bits_down = nullptr;
+    pl.scales_up = pl.scales_down = nullptr;
+    pl.blk_sums = nullptr;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    bool given;
+    int rc = prepare_scales(&pl, 1, (flags & FO_FORCE_SCALE) != 0, scales, 0, st, &given);
+    if (rc) return rc;
+    const uint64_t len = party == FO_PARTY_SERVER ? pl.ntot : pl.p.d;
+    return launch_encode(&pl, nullptr, g, 0, len, 1, party, round, given, bits, 0, scales, 0, pl.buf_a, 0, st);
 }
