@@ -21,16 +21,24 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
-# HBM bytes per launch on workload c3 measured with rocprofv3 --pmc (FETCH_SIZE scaled by 2.000, WRITE_SIZE
-# by 1.000, the factors of a 1 GiB copy; profiles/c3_fo_step_hbm_traffic.md), keyed by kernel name.  For the
-# kernels launched with two batch sizes per step the figure is the per-step sum divided by two.
-MEASURED_TRAFFIC = {
-    "k_strided<ENC_FIRST>": 3783807574,
-    "k_contig<IN_F32,OUT_PACK>": (2214798093 + 138661273) // 2,
-    "k_strided<SERVER>": 1208240742,
-    "k_declow": (1140953485 + 71407510) // 2,
-    "k_strided<DEC_LAST>": 271920344,
-}
+TRAFFIC_TABLE = os.path.join(ROOT, "profiles", "hbm_traffic_table.txt")
+
+
+def measured_traffic(workload, block_log2, eps_mode, K, kernel):
+    """HBM bytes per launch of `kernel` as rocprofv3 --pmc measured them (FETCH_SIZE, WRITE_SIZE, each scaled by what
+    the same counter reads for a 1 GiB copy), from the table kept next to the rocprofv3 summaries under profiles/.
+    Returns (bytes, source file) or (None, None) when the table has no row for this workload and kernel."""
+    try:
+        lines = open(TRAFFIC_TABLE).read().splitlines()
+    except OSError:
+        return None, None
+    for ln in lines:
+        f = ln.split()
+        if len(f) < 7 or ln.startswith("#"):
+            continue
+        if (f[0], int(f[1]), f[2], int(f[3]), f[4]) == (workload, block_log2, eps_mode, K, kernel):
+            return int(f[5]), f[6]
+    return None, None
 
 
 def main():
@@ -120,48 +128,74 @@ def main():
     prof = plan.fo_profile_end()
     sec = (t_end - t_start) / args.steps
     value = 4.0 * d * M / sec / 1e9
+    # Median step time, from a second pass of `steps` steps with one event between steps (kept out of the timed
+    # region above: an event keeps the next step's first kernel from overlapping the tail of the last one).
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the launch stream
+    marks[0].record()
+    for k in range(args.steps):
+        plan.fo_step(gs, x, delta, 2000 + k)
+        marks[k + 1].record()
+    torch.cuda.synchronize()
+    step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
+    med_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
 
     # roofline of the dominant kernel
     per_kernel = {k: (l, ms) for k, (l, ms) in breakdown.items()}
     launches, total_ms = prof[dom]
     avg_ms = total_ms / launches
-    # kernels launched with two different batch sizes per step have a per-step algorithmic figure
+    # Bytes per step, per kernel.  `model`: the two-pass byte model the workload is priced with (every operand once,
+    # 4-byte intermediates between passes).  `moved`: the operands as this build lays them out (the decode side's
+    # intermediates are int16), i.e. what the kernels have to move through HBM; rocprofv3's counters agree with it.
     W8 = n // 8
-    per_step = {
+    ind = args.eps_mode == "independent"
+    pair = "k_contig_pair" in per_kernel
+    n_low = (M + 1) if not pair else 1                       # vectors through the encode's low pass
+    n_dlow = (M + (0 if "k_decode_pair" in per_kernel else 1)) if ind else 1
+    model = {
         "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
         # with blocks of 2^16 the workers' encode is one pass (k_contig_pair); only the server re-encodes in two
-        "k_contig<IN_F32,OUT_PACK>": ((M + 1) if "k_contig_pair" not in per_kernel else 1) * (4 * n + W8),
+        "k_contig<IN_F32,OUT_PACK>": n_low * (4 * n + W8),
         "k_contig_pair": M * (4 * d + W8),
-        "k_declow": ((M + (0 if "k_decode_pair" in per_kernel else 1)) if args.eps_mode == "independent" else 1) * (W8 + 4 * n),
-        "k_strided<SERVER>": (M * 4 * n + 4 * n) if args.eps_mode == "independent" else 8 * n,
+        "k_declow": n_dlow * (W8 + 4 * n),
+        "k_strided<SERVER>": (M * 4 * n + 4 * n) if ind else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_mean_tile": M * W8 + 4 * n,
+        "k_server_tile": M * W8 + W8,
         "k_shall": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
-        "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8),
+        "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8 if "k_mean_tile" in per_kernel else 0),
         "k_decode_tile": W8 + 8 * d,
         "k_decode_pair": W8 + 8 * d,
     }
-    step_bytes = per_step.get(dom)
+    moved = dict(model)
+    moved["k_declow"] = n_dlow * (W8 + 2 * n)
+    moved["k_strided<SERVER>"] = (M * 2 * n + 4 * n) if ind else 8 * n
+    moved["k_strided<DEC_LAST>"] = 2 * n + 8 * d
+    step_bytes = model.get(dom)
     bytes_per_launch = step_bytes * args.steps / launches if step_bytes else None
     achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9 if bytes_per_launch else None
+    traffic, traffic_src = measured_traffic(args.workload, blk, args.eps_mode, args.K, dom)
+    step_model = sum(v for k, v in model.items() if k in per_kernel)
+    step_moved = sum(v for k, v in moved.items() if k in per_kernel)
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1) if achieved else None, "peak": HBM_PEAK_GBS,
         "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4) if achieved else None,
-        "traffic": MEASURED_TRAFFIC.get(dom) if (args.workload == "c3" and args.eps_mode == "independent" and args.K == 1) else None,
+        "traffic": traffic, "traffic_source": traffic_src,
         "avg_launch_ms": round(avg_ms, 4), "bytes_per_launch": bytes_per_launch,
         "kernel_ms_per_step": {k: round(ms / nbreak, 4) for k, (l, ms) in sorted(per_kernel.items())},
         "kernel_ms_per_step_from": f"an untimed pass of {nbreak} steps with every kernel bracketed by events",
-        "step_model_bytes": sum(v for k, v in per_step.items() if k in per_kernel),
+        # whole step: the headline fraction is on the bytes this build moves; the model's bytes are given beside it
+        "step_moved_bytes": step_moved, "step_model_bytes": step_model,
+        "step_frac_of_hbm_peak": round(step_moved / sec / 1e9 / HBM_PEAK_GBS, 4),
+        "step_frac_of_hbm_peak_on_model_bytes": round(step_model / sec / 1e9 / HBM_PEAK_GBS, 4),
     }
-    roofline["step_frac_of_hbm_peak"] = round(roofline["step_model_bytes"] / sec / 1e9 / HBM_PEAK_GBS, 4)
     if copy_gbs:
         roofline["device_copy_gbs"] = round(copy_gbs, 1)   # what a plain copy of 1 GiB reaches on this machine
 
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import fo_oracle as O
-        Ms = min(8, M)                                   # bounded sample: the first Ms workers, full d
+        Ms = M                                           # the whole round: all M workers, full d
         nthreads = max(1, min(Ms, 16, os.cpu_count() or 1))
         p = O.params(d=d, M=Ms, block_log2=blk, K=args.K, seed=seed, eps_mode=int(eps_mode), server_scale=int(srv))
         xo = np.zeros(d, dtype=np.float64)
@@ -169,14 +203,15 @@ def main():
         O.round_trip(p, gs_host[:Ms], xo, delta, 0, nthreads=nthreads)
         c1 = time.perf_counter()
         cpu = {"value": round(4.0 * d * Ms / (c1 - c0) / 1e9, 4), "unit": "GB/s", "cores": nthreads, "kind": "oracle",
-               "sample": f"one full round trip of the same workload with the first {Ms} of {M} workers "
-                         f"(d={d}, n={n}), fp64; the {Ms} encodes run one per thread, the server and the "
-                         f"downlink decode on one thread; {c1 - c0:.1f} s"}
+               "sample": f"one full round trip of the same workload, all {M} workers (d={d}, n={n}), fp64; the "
+                         f"encodes run one per thread on {nthreads} threads, the server and the downlink decode on "
+                         f"one thread; {c1 - c0:.1f} s"}
 
     out = {
         "metric": "GB/s of fp32 gradient encoded+aggregated+decoded; % of HBM roofline",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": round(sec * 1e3, 4), "ms_per_step_median": round(med_ms, 4),
+        "value_at_median_step": round(4.0 * d * M / (med_ms * 1e-3) / 1e9, 2), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: d={d} fp32 padded to n={n}, M={M} workers, "
                                f"{'full-length' if blk == 0 else f'blocks of 2^{blk}'} randomized FWHT, uniform dither, "

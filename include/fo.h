@@ -40,6 +40,9 @@
  * gbar, the usual case) and alpha sqrt(ln b) times smaller, which cuts the downlink's error term by that
  * factor squared.
  *
+ * Amplitudes a caller supplies (FO_FORCE_SCALE, fo_decode, fo_server_aggregate) may have either sign: the decoder is
+ * linear in them, so a negated amplitude gives the negated vector on every path.
+ *
  * Shared worker eps (FO_EPS_SHARED_WORKERS, a variant the paper does not have).  When every worker
  * uses the same eps_t and the same amplitude, linearity of H^T turns the server's M decodes into one:
  * gbar = (lambda / M) D_eps H^T (2 c - M) with c the per-coordinate count of set bits over the M
@@ -52,7 +55,8 @@
  * H D_eps gbar = (lambda / M)(2 c - M) and the server needs no transform at all, only the count, the dither
  * and the comparison.  This drops the independence of eps^s that the paper's server lemma assumes; it is a
  * flagged variant, never the default.  gbar_or_null still works (one inverse transform, for checking).
- * Both shared modes are built for transform lengths up to 2^25.
+ * Both shared modes are built for transform lengths up to 2^25 and need M b < 2^31 (the summed sign vectors
+ * are transformed in 32-bit integers).
  *
  * Averaged downlink quantiser (K > 1).  The server's message is Q_{lambda^s,K} of Def. 3.2: the mean of K
  * one-bit quantisers with independent dithers, which cuts the downlink's error term by K (Lemma "Second
@@ -104,7 +108,7 @@ extern "C" {
 #define FO_MAX_K 255u
 
 typedef struct {
-    uint64_t d;          /* logical gradient length, 1 <= d, padded length <= 2^30        */
+    uint64_t d;          /* logical gradient length, 1 <= d; one transform: d <= 2^30; blocked: ntot <= 2^32 */
     uint32_t M;          /* number of workers (the paper's N), 1 .. FO_MAX_WORKERS        */
     uint32_t block_log2; /* 0, or 6 .. 30                                                 */
     uint32_t K;          /* averaging count of the downlink quantizer (Def. 3.2), 1 .. FO_MAX_K */

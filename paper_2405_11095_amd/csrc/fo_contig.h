@@ -455,8 +455,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
                     uint64_t word[4];
 #pragma unroll
                     for (int s = 0; s < 4; ++s) word[s] = __ballot(((cnt[s] >> p) & 1u) != 0u);
-                    settle_ballots(word[0], word[1], word[2], word[3]);
-                    static_for<4>([&](auto sc) {
+                            static_for<4>([&](auto sc) {
                         constexpr int s = decltype(sc)::value;
                         constexpr int r = 2 * g + (s & 1) + 32 * (s >> 1);
                         lo[p] = write_lane<r>(lo[p], (uint32_t)word[s]);
@@ -500,7 +499,6 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
                 word[s] = __ballot(tv >= 0.f);
             }
             // the 64-bit word of register r goes to lane r: one write into that lane per half
-            settle_ballots(word[0], word[1], word[2], word[3]);
             static_for<4>([&](auto sc) {
                 constexpr int s = decltype(sc)::value;
                 constexpr int r = 2 * g + (s & 1) + 32 * (s >> 1);

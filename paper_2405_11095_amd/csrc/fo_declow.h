@@ -176,9 +176,10 @@ __device__ __forceinline__ constexpr uint32_t declow_reg_dword(int r)
     return ((uint32_t)((r >> 3) & 1) << 6) | ((uint32_t)(r >> 4) << 7) | ((uint32_t)(r & 7) << 11);
 }
 
+// (Kernels that are not templates are static: these headers are included by several translation units.)
 // Uses src, src_stride (64-bit words between slots), dst, dst_stride (int16 elements between slots) and W
 // of the argument block; the transform length is at least 2^15, so every tile is complete.
-__global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
+static __global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs a)
 {
     __shared__ uint32_t xbuf[kXWords];
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;

@@ -126,22 +126,17 @@ __device__ __forceinline__ void static_for(F &&f)
     }
 }
 
+// v_writelane_b32 as the compiler's own intrinsic (this toolchain has no clang builtin for it, so the LLVM
+// intrinsic is bound by name).  Unlike inline assembly, the compiler sees the instruction and inserts the wait
+// states gfx950 needs between a vector compare that writes a scalar register pair and a vector instruction that
+// reads it (two; back to back the lane write can pick up the register's previous contents).
+extern "C" __device__ int fo_llvm_writelane(int value, int lane, int old) __asm("llvm.amdgcn.writelane.i32");
+
 // Returns v with lane LANE replaced by the wave-uniform value s (every other lane keeps its own).
-// v_writelane_b32 picks up a scalar register that a vector instruction (a compare) has just written
-// only after a few wait states: measured on gfx950, back-to-back use gives stale data now and then.
-// Callers put settle_ballots() between the compares and the lane writes.
 template <int LANE>
 __device__ __forceinline__ uint32_t write_lane(uint32_t v, uint32_t s)
 {
-    asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(v) : "s"(s), "n"(LANE));
-    return v;
-}
-
-// Orders four ballots before everything that follows and adds five wait states, whatever order the
-// compiler gave the compares; the idle cycles go to the other waves of the SIMD.
-__device__ __forceinline__ void settle_ballots(uint64_t w0, uint64_t w1, uint64_t w2, uint64_t w3)
-{
-    asm volatile("s_nop 4" ::"s"(w0), "s"(w1), "s"(w2), "s"(w3));
+    return (uint32_t)fo_llvm_writelane((int)s, LANE, (int)v);
 }
 
 // One Walsh-Hadamard stage on lane bit 5 (partner = lane ^ 32).  v_permlane32_swap trades the

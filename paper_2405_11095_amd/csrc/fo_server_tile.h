@@ -80,9 +80,9 @@ __global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs 
         for (int r = 0; r < 32; ++r) {
             const uint32_t D = dtl + declow_reg_dword(r);
             const uint32_t w = epsw[D >> 4];
-            const uint32_t cbits = __float_as_uint(lam[D >> (S - 1u)]); // non-negative: the eps sign goes into bit 31
-            acc[2 * r] = fmaf((float)v[r].x, __uint_as_float(((w >> eshift) << 31) | cbits), acc[2 * r]);
-            acc[2 * r + 1] = fmaf((float)v[r].y, __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits), acc[2 * r + 1]);
+            const uint32_t cbits = __float_as_uint(lam[D >> (S - 1u)]); // the eps bit is added into bit 31: a flip of the sign, whatever it was
+            acc[2 * r] = fmaf((float)v[r].x, __uint_as_float(((w >> eshift) << 31) + cbits), acc[2 * r]);
+            acc[2 * r + 1] = fmaf((float)v[r].y, __uint_as_float(((w >> (eshift + 1u)) << 31) + cbits), acc[2 * r + 1]);
         }
     }
 
@@ -142,8 +142,8 @@ __global__ __launch_bounds__(kThreads, 4) void k_decode_tile(const ContigArgs a)
         const uint32_t D = dt + declow_reg_dword(r);
         const uint32_t w = epsw[D >> 4];
         const uint32_t cbits = __float_as_uint(lam[D >> (S - 1u)]);
-        const float y0 = (float)v[r].x * __uint_as_float(((w >> eshift) << 31) | cbits);
-        const float y1 = (float)v[r].y * __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits);
+        const float y0 = (float)v[r].x * __uint_as_float(((w >> eshift) << 31) + cbits);
+        const float y1 = (float)v[r].y * __uint_as_float(((w >> (eshift + 1u)) << 31) + cbits);
         if (2ull * D + 1 < room) {
             float2 q = dst[D];
             if (a.store_mode == STORE_SET) q = make_float2(y0, y1);
@@ -180,7 +180,7 @@ __device__ __forceinline__ PairGroup pair_group()
 }
 
 // k_decode_tile for transforms of exactly 2^16 points; same uses of the argument block.
-__global__ __launch_bounds__(2 * kThreads) void k_decode_pair(const ContigArgs a)
+static __global__ __launch_bounds__(2 * kThreads) void k_decode_pair(const ContigArgs a)
 {
     __shared__ uint32_t lds[2 * (kXWords + kEpsWords)];
     const PairGroup g = pair_group();
@@ -214,8 +214,8 @@ __global__ __launch_bounds__(2 * kThreads) void k_decode_pair(const ContigArgs a
         for (int q = 0; q < 8; ++q) {
             const uint32_t D = g.dt + declow_reg_dword(8 * decltype(G)::value + q);
             const uint32_t e = epsw[D >> 4];
-            const float y0 = (float)w[2 * q] * __uint_as_float(((e >> g.eshift) << 31) | cbits);
-            const float y1 = (float)w[2 * q + 1] * __uint_as_float(((e >> (g.eshift + 1u)) << 31) | cbits);
+            const float y0 = (float)w[2 * q] * __uint_as_float(((e >> g.eshift) << 31) + cbits);
+            const float y1 = (float)w[2 * q + 1] * __uint_as_float(((e >> (g.eshift + 1u)) << 31) + cbits);
             if (2ull * D + 1 < room) {
                 float2 o = dst[D];
                 if (a.store_mode == STORE_SET) o = make_float2(y0, y1);

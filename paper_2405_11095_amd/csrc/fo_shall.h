@@ -23,14 +23,14 @@ struct ShallArgs {
 
 // ---- measured-norm server amplitude for this mode: ||gbar_block||^2 = (lambda / M)^2 sum_i (2 c_i - M)^2, and the
 // sum is an integer, so it is accumulated exactly (and in any order) with 64-bit integer atomics.
-__global__ void k_zero_u64(unsigned long long *p, uint64_t n)
+static __global__ void k_zero_u64(unsigned long long *p, uint64_t n)
 {
     const uint64_t i = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0ull;
 }
 
 // Same fetch-and-count as k_shall; sums[j] += sum over block j of (2 c - M)^2.
-__global__ __launch_bounds__(256) void k_shall_sumsq(const ShallArgs a, unsigned long long *sums)
+static __global__ __launch_bounds__(256) void k_shall_sumsq(const ShallArgs a, unsigned long long *sums)
 {
     __shared__ unsigned long long part[16];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
@@ -75,14 +75,14 @@ __global__ __launch_bounds__(256) void k_shall_sumsq(const ShallArgs a, unsigned
 }
 
 // lambda^s_j = coef * (lambda_j / M) * sqrt(sums[j]),  coef = alpha_s sqrt(ln b / b)
-__global__ void k_shall_scales(const unsigned long long *sums, const float *lam, uint64_t nblocks, uint32_t M, float coef,
+static __global__ void k_shall_scales(const unsigned long long *sums, const float *lam, uint64_t nblocks, uint32_t M, float coef,
                                float *lam_s)
 {
     const uint64_t j = blockIdx.x * (uint64_t)blockDim.x + threadIdx.x;
     if (j < nblocks) lam_s[j] = coef * (lam[j] / (float)M) * (float)sqrt((double)sums[j]);
 }
 
-__global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
+static __global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
 {
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t q = (uint64_t)blockIdx.x * 4u + (threadIdx.x >> 6); // group of four words

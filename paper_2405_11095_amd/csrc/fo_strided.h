@@ -456,13 +456,13 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             } else {
                 __syncthreads(); // publishes the eps table
             }
-            // acc += (+-c) * value: the eps sign goes into the (non-negative) coefficient's sign bit
+            // acc += (+-c) * value: the eps bit is added into the coefficient's sign bit (a flip, whatever the sign was)
             const uint32_t cbits = __float_as_uint(a.scales[(uint64_t)m * a.scales_stride + gb] * a.out_coef);
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
                 const uint32_t w = epsm[(ut_out >> 5) + (upair_out(p) >> 5)];
-                acc[2 * p] = fmaf(buf[2 * p], __uint_as_float(((w >> eshift) << 31) | cbits), acc[2 * p]);
-                acc[2 * p + 1] = fmaf(buf[2 * p + 1], __uint_as_float(((w >> (eshift + 1u)) << 31) | cbits), acc[2 * p + 1]);
+                acc[2 * p] = fmaf(buf[2 * p], __uint_as_float(((w >> eshift) << 31) + cbits), acc[2 * p]);
+                acc[2 * p + 1] = fmaf(buf[2 * p + 1], __uint_as_float(((w >> (eshift + 1u)) << 31) + cbits), acc[2 * p + 1]);
             }
         };
         request(0);

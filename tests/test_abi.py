@@ -55,6 +55,7 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(server_scale=2) == B.EINVAL
     assert create(d=(1 << 30) + 1) == B.EINVAL
     assert create(d=(1 << 26), eps_mode=1) == B.EINVAL          # shared eps is built up to n = 2^25
+    assert create(d=(1 << 25), M=64, eps_mode=1) == B.EINVAL    # M b = 2^31 would overflow the summed sign vectors
     assert lib.fo_plan_create(None, None) == B.EINVAL
     # NULL plan in the hot calls
     assert lib.fo_encode(None, None, 0, 0, 0, None, None, None) == B.EINVAL

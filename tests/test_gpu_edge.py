@@ -321,7 +321,7 @@ def test_c2_sparse_workload(env):
     assert np.max(np.abs(gs[0])) / np.sqrt(np.mean(gs[0].astype(np.float64) ** 2)) > 5 * np.max(np.abs(r["z"])) / np.sqrt(np.mean(r["z"] ** 2))
 
 
-@pytest.mark.parametrize("blk", [12, 16])
+@pytest.mark.parametrize("blk", [10, 12, 14, 16])
 def test_c4_full_size_sampled_blocks(env, blk):
     """d = 2^27, M = 8, layered dynamic range: the whole round on the GPU, oracle on sampled blocks."""
     O, B, inputs, dev = env
@@ -513,3 +513,40 @@ def test_resume_needs_only_x_and_the_round(env):
     assert torch.equal(z, x)
     whole.close()
     second.close()
+
+
+@pytest.mark.parametrize("d,blk,M", [(50_000, 12, 3), (30_000, 0, 2), ((1 << 17) + 9, 16, 2), (300_000, 0, 3)])
+def test_negative_amplitudes_flip_the_decoded_vector(env, d, blk, M):
+    """The decoder is linear in the amplitude, D = lambda D_eps H^T q (Def. 3.8): a caller-supplied negative
+    amplitude gives minus the vector of the positive one on every kernel path (single tile, pair, two-pass), and in
+    the server's mean a worker with a negated amplitude enters with the opposite sign."""
+    import torch
+    O, B, inputs, dev = env
+    plan = B.Plan(d=d, M=M, block_log2=blk, seed=99)
+    W, nb, nt = plan.W, plan.nblocks, plan.ntot
+    bits = torch.zeros((M, W), dtype=torch.int64, device=dev)
+    lam = torch.zeros((M, nb), dtype=torch.float32, device=dev)
+    for m in range(M):
+        plan.fo_encode(torch.from_numpy(inputs.gaussian(d, m)).to(dev), 4, m, bits[m], lam[m])
+    out_p = torch.zeros(d, dtype=torch.float32, device=dev)
+    out_n = torch.zeros(d, dtype=torch.float32, device=dev)
+    plan.fo_decode(bits[0], lam[0], 4, 0, out_p)
+    plan.fo_decode(bits[0], -lam[0], 4, 0, out_n)
+    torch.cuda.synchronize()
+    assert float(out_p.abs().max()) > 0 and torch.equal(out_n, -out_p)
+    # server: negating worker 1's amplitudes moves the mean by -2/M times that worker's decoded vector
+    bd = torch.zeros((plan.planes, W), dtype=torch.int64, device=dev)
+    ls = torch.zeros(nb, dtype=torch.float32, device=dev)
+    g1 = torch.zeros(nt, dtype=torch.float32, device=dev)
+    g2 = torch.zeros(nt, dtype=torch.float32, device=dev)
+    plan.fo_server_aggregate(bits, lam, 4, bd, ls, g1)
+    lam2 = lam.clone()
+    lam2[1] = -lam2[1]
+    plan.fo_server_aggregate(bits, lam2, 4, bd, ls, g2)
+    torch.cuda.synchronize()
+    p = O.params(d=d, M=M, block_log2=blk, seed=99)
+    dec1 = O.decode(p, O.unpack(bits[1].cpu().numpy().view(np.uint64), nt), lam[1].cpu().numpy().astype(np.float64), 4, 1)
+    want = g1.cpu().numpy().astype(np.float64) - 2.0 * dec1 / M
+    from tests.parity import rel_l2
+    assert rel_l2(g2.cpu().numpy(), want) < 1e-5
+    plan.close()

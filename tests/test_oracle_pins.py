@@ -551,3 +551,27 @@ def test_oracle_is_clean_under_host_sanitizers(tmp_path):
     run = subprocess.run([exe], capture_output=True, text=True, timeout=300)
     assert run.returncode == 0, run.stdout + run.stderr
     assert run.stdout.count("checksum") == 5
+
+
+def test_pack_layout_against_numpy_little_endian_bits(oracle):
+    """Packing format: word w, bit j <-> coordinate 64 w + j, set bit = +1.  Pinned to NumPy's own little-endian
+    bit (un)packing of the same bytes and to single-coordinate spikes, so that a slip on one side or a consistent
+    one on both sides of pack / unpack (bit order inside a word, word order, polarity) fails here."""
+    rng = np.random.default_rng(77)
+    n = 64 * 37
+    q = (2 * rng.integers(0, 2, n) - 1).astype(np.int32)
+    bits = oracle.pack(q)
+    assert bits.dtype == np.uint64 and bits.size == n // 64
+    want = np.packbits((q > 0).astype(np.uint8), bitorder="little").view("<u8")
+    assert np.array_equal(bits, want)
+    got = np.unpackbits(bits.view(np.uint8), bitorder="little")[:n]
+    assert np.array_equal(got.astype(bool), q > 0)
+    assert np.array_equal(oracle.unpack(want, n), q)
+    for i in (0, 1, 31, 32, 63, 64, 65, 127, 64 * 36 + 63):
+        e = -np.ones(n, dtype=np.int32)
+        e[i] = 1
+        b = oracle.pack(e)
+        assert int(b[i // 64]) == 1 << (i % 64) and np.count_nonzero(b) == 1
+        w = np.zeros(n // 64, dtype=np.uint64)
+        w[i // 64] = np.uint64(1) << np.uint64(i % 64)
+        assert np.array_equal(oracle.unpack(w, n), e)
