@@ -159,11 +159,11 @@ def main():
         "k_declow": n_dlow * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if ind else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
-        "k_mean_tile": M * W8 + 4 * n,
+        "k_mean_mfma": M * W8 + 4 * n,
         "k_server_tile": M * W8 + W8,
         "k_shall": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
-        "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8 if "k_mean_tile" in per_kernel else 0),
+        "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8 if "k_mean_mfma" in per_kernel else 0),
         "k_decode_tile": W8 + 8 * d,
         "k_decode_pair": W8 + 8 * d,
     }

@@ -118,6 +118,7 @@ int plan_geometry(const fo_params &q, fo_plan *pl)
     pl->p = q;
     pl->stats = nullptr;
     pl->round_dev = nullptr;
+    pl->num_cus = 256;
     if (q.block_log2 == 0) {
         uint32_t k = 6;
         while (((uint64_t)1 << k) < q.d) ++k;
@@ -168,6 +169,15 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
         if (rc) { delete pl; return rc; }
     }
 
+    {
+        int dev = 0, cus = 0;
+        if (!hip_ok(hipGetDevice(&dev), "hipGetDevice") ||
+            !hip_ok(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev), "hipDeviceGetAttribute")) {
+            delete pl;
+            return FO_EHIP;
+        }
+        if (cus > 0) pl->num_cus = (uint32_t)cus;
+    }
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t sz_a = pl->npass ? up((size_t)q.M * pl->ntot * 4) : 0;
     const size_t sz_b = up(pl->ntot * 4);

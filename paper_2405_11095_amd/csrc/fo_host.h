@@ -30,7 +30,7 @@ enum KernelId {
     KID_DEC_HIGH,       // k_strided<DEC_LAST>
     KID_SERVER_HIGH,    // k_strided<SERVER> / k_strided<SHARED>
     KID_COUNT_LOW,      // k_contig<IN_COUNT,*>
-    KID_SERVER_TILE,    // k_mean_tile
+    KID_SERVER_TILE,    // k_mean_mfma
     KID_SHALL,          // k_shall
     KID_ENC_PAIR,       // k_contig_pair
     KID_DEC_PAIR,       // k_decode_pair
@@ -40,7 +40,7 @@ enum KernelId {
 inline const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_tile", "k_shall", "k_contig_pair", "k_decode_pair", "scale kernels",
+    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_mfma", "k_shall", "k_contig_pair", "k_decode_pair", "scale kernels",
 };
 
 struct Profiler {
@@ -64,6 +64,7 @@ struct fo_plan {
     uint32_t npass;      // strided passes: 0, 1 or 2
     uint32_t hb[2];      // stages of each strided pass (pass 0 is adjacent to the contiguous tile)
     uint32_t planes;     // bit planes of the downlink message: ceil(log2(K + 1))
+    uint32_t num_cus;    // compute units of the device the plan was made on
     float coef_lambda, sqrtb, rsqrtb, coef_s;
     float coef_lambda_s; // alpha_s sqrt(ln b / b): measured-norm rule for the server
     // scratch (device)
@@ -130,10 +131,12 @@ inline bool args_ok(const ShallArgs &z, int)
     return z.bits_up && z.dst && z.lam && z.lam_s && z.M >= 1 && z.M <= FO_MAX_WORKERS && z.K >= 1 && z.planes >= 1;
 }
 inline bool args_ok(const ShallArgs &z, unsigned long long *sums, int kid) { return sums && args_ok(z, kid); }
+inline bool args_ok(const ServerTileArgs &s, uint32_t ntiles, int kid);
 inline bool args_ok(const ServerTileArgs &s, int)
 {
     return s.enc.src && s.bits_up && s.scales_up && s.M >= 1 && s.M <= FO_MAX_WORKERS && s.enc.S >= 6 && s.enc.S <= 15;
 }
+inline bool args_ok(const ServerTileArgs &s, uint32_t ntiles, int kid) { return ntiles >= 1 && args_ok(s, kid); }
 inline bool args_ok(const StridedArgs &s, const PtrTab &tab, int kid)
 {
     if (!s.dst) return false;

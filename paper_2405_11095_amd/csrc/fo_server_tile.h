@@ -1,12 +1,9 @@
-// Kernels for transforms that fit one tile (transform length b <= 2^15, whole or blocked), built on declow_tile
-// (popcount + packed int16) with the amplitude, the eps flip and the store or accumulation done in its output
-// layout.
-//   k_mean_tile  : the server's mean gbar = (1/M) sum_n lambda_n D_eps_n H^T q_n (Def. 3.8, eq. "server average"):
-//                  per tile, the M messages are decoded one after the other and summed in registers; the M decoded
-//                  vectors never exist in memory (M * 4 KiB of packed signs in, 128 KiB of fp32 out per tile).
-//                  The re-encode of the mean is the ordinary encode kernel.  (A variant that also re-encoded the
-//                  tile in the same kernel was measured slower: it needs so many registers that one 512-thread
-//                  workgroup fills a CU.)
+// Kernels for transforms that fit one tile (transform length b <= 2^15, whole or blocked).  The decoders are built on
+// declow_tile (popcount + packed int16) with the amplitude, the eps flip and the store done in its output layout.
+//   k_mean_mfma  : the server's mean gbar = (1/M) sum_n lambda_n D_eps_n H^T q_n (Def. 3.8, eq. "server average"):
+//                  per tile, the M messages are decoded one after the other on the matrix cores (fo_mfma.h) and summed
+//                  in registers; the M decoded vectors never exist in memory (M * 4 KiB of packed signs in, 128 KiB
+//                  of fp32 out per tile).  The re-encode of the mean is the ordinary encode kernel.
 //   k_decode_tile: one party's decoder with store / accumulate / SGD update.
 //   k_decode_pair: the decoder for transforms of exactly 2^16 points: a workgroup of 1024 threads, two groups of
 //                  512 on the two tiles of a block, sixteenth stage through both groups' exchange buffers
@@ -15,6 +12,7 @@
 //                  than the two-pass path, whose second pass also starts the re-encode.)
 #pragma once
 #include "fo_declow.h"
+#include "fo_mfma.h"
 
 namespace fo {
 
@@ -26,75 +24,138 @@ struct ServerTileArgs {
     float coef;               // value = lambda_n * coef * (half-valued integer): 2 / (sqrt(b) M)
 };
 
-// SC: compiled for transforms of 2^SC points (the block lengths of the blocked workload), 0: length read at run time.
-template <int SC>
-__global__ __launch_bounds__(kThreads, 4) void k_mean_tile(const ServerTileArgs sa)
+// The server's mean on the matrix cores: per tile, the M messages are decoded one after the other by the three
+// matrix products of fo_mfma.h and summed in registers, acc += (lambda_n c) eps_n (H^T q_n) / 2.  Any transform
+// length 2^6 .. 2^15.  A workgroup walks over tiles blockIdx.x, blockIdx.x + gridDim.x, ... (its constant operands
+// do not depend on the tile).  Two exchange buffers and two eps tables are used in turn, and the loop is skewed:
+// between two barriers a wave runs stages 1 and 2 of worker m + 1 and stage 3 plus the accumulation of worker m.
+// The finished tile goes through LDS once more so that the stores to memory are whole 1 KiB rows per wave.
+static __global__ __launch_bounds__(kMfThreads) void k_mean_mfma(const ServerTileArgs sa, const uint32_t ntiles)
 {
-    // two sets of tables used in turn, so that the worker loop needs no barrier of its own
-    __shared__ uint32_t lds[kXWords + 2 * (kEpsWords + kLamWords)];
-    uint32_t *const xbuf = lds;
-    uint32_t *const tables = lds + kXWords;
+    __shared__ uint32_t lds[2 * kMfXWords + 2 * kMfEpsWords];
+    static_assert(2 * kMfXWords >= kTile + 64, "the output transposition reuses the exchange buffers");
+    char *const xb = reinterpret_cast<char *>(lds);
+    uint32_t *const tables = lds + 2 * kMfXWords;
     const ContigArgs &a = sa.enc;
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
-    const uint32_t tile = blockIdx.x;
-    const uint32_t S = SC ? (uint32_t)SC : a.S;
+    const uint32_t col = lane & 31u, h = lane >> 5;
+    const uint32_t S = a.S;
     uint32_t rk1, rlo;
     resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
-    const uint64_t base = (uint64_t)tile << kTileLog2;
-    const uint32_t nblk_tile = kTile >> S;
-    const uint64_t blk0 = (uint64_t)tile * nblk_tile;
-    const uint32_t dt = lane | (wave << 8);      // thread part of the dword index in layout LC
-    const uint32_t eshift = (lane & 15u) << 1;   // bit of the pair's first coordinate inside its eps word
 
-    float acc[64];
-#pragma unroll
-    for (int r = 0; r < 64; ++r) acc[r] = 0.f;
+    MfConst k;
+    mf_build_constants(k, S, lane, wave);
 
-    for (uint32_t m = 0; m < sa.M; ++m) {
-        // tables of worker m for this tile: 1024 eps words (256 generator calls) and one coefficient per block.
-        // The barriers inside declow_tile publish them; every wave passes those only when it is done with worker
-        // m-1, so the set of worker m-2 may be overwritten without waiting.
-        uint32_t *const epsw = tables + (m & 1u) * (kEpsWords + kLamWords);
-        float *const lam = reinterpret_cast<float *>(epsw + kEpsWords);
-        if (t < 256u) {
-            const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, m };
-            uint32_t w[4];
-            philox((uint32_t)(base >> 7) + t, key_eps, w);
+    // exchange addresses (bytes): write row (b1..b4 | b5) = 2 h (+ register part), column b6..b10 = col, dword = slab
+    // (swizzled by the column); read row = col, column 2 wave + gi, 16-byte piece h (and 2 + h)
+    const uint32_t xw = 2u * h * kMfRowBytes + col * 64u + 4u * (wave ^ (col >> 2));
+    const uint32_t xr = col * kMfRowBytes + 2u * wave * 64u + 16u * h;
+    // per column group gi: tile-local coordinate of this lane's values without the register part
+    uint32_t ibase[2];
+    float dcoff[2];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) epsw[t * 4u + j] = w[j];
-        }
-        if (t < nblk_tile) {
-            const uint64_t gb = blk0 + t;
-            lam[t] = gb < a.nblocks ? sa.scales_up[(uint64_t)m * a.nblocks + gb] * sa.coef : 0.f;
-        }
-        s16x2 v[32];
-        uint32_t tl = t;
-        asm volatile("" : "+v"(tl));
-        declow_tile<SC>(reinterpret_cast<const uint32_t *>(sa.bits_up + (uint64_t)m * a.W), a.W, tile, S, xbuf, xbuf, v, tl);
-        __syncthreads(); // the exchange buffer is read; the next worker's first exchange may write it
-        // the table addresses are recomputed for every worker: hoisted out of the loop they would hold 64 registers
-        // next to the 64 accumulators
-        uint32_t dtl = dt;
-        asm volatile("" : "+v"(dtl));
-#pragma unroll
-        for (int r = 0; r < 32; ++r) {
-            const uint32_t D = dtl + declow_reg_dword(r);
-            const uint32_t w = epsw[D >> 4];
-            const uint32_t cbits = __float_as_uint(lam[D >> (S - 1u)]); // the eps bit is added into bit 31: a flip of the sign, whatever it was
-            acc[2 * r] = fmaf((float)v[r].x, __uint_as_float(((w >> eshift) << 31) + cbits), acc[2 * r]);
-            acc[2 * r + 1] = fmaf((float)v[r].y, __uint_as_float(((w >> (eshift + 1u)) << 31) + cbits), acc[2 * r + 1]);
-        }
+    for (int gi = 0; gi < 2; ++gi) {
+        ibase[gi] = (col & 1u) | (h << 3) | ((2u * wave + gi) << 6) | ((col >> 1) << 11);
+        // the constant that the bits-for-signs shortcut leaves on the first coordinate of every block (register 0)
+        dcoff[gi] = ((ibase[gi] & ((1u << S) - 1u)) == 0u) ? (float)(1u << (S - 1u)) : 0.f;
     }
+    const uint32_t esh = (col & 1u) + 8u * h; // eps bits of this lane: b0 and b3 from the lane, the rest per register
+    const uint32_t *const words = reinterpret_cast<const uint32_t *>(sa.bits_up);
 
-    // the mean of the tile, natural order
-    {
-        float2 *gq = reinterpret_cast<float2 *>(const_cast<void *>(a.src)) + (base >> 1);
-        const uint64_t room = a.len_in > base ? (a.len_in - base) >> 1 : 0; // pairs of this tile inside the buffer
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+        const uint64_t base = (uint64_t)tile << kTileLog2;
+        // amplitudes: loaded one worker ahead from a clamped (always valid) address, zeroed by cf[] outside the vector
+        uint32_t blk[2];
+        float cf[2];
 #pragma unroll
-        for (int r = 0; r < 32; ++r) {
-            const uint32_t D = dt + declow_reg_dword(r);
-            if (D < room) gq[D] = make_float2(acc[2 * r], acc[2 * r + 1]);
+        for (int gi = 0; gi < 2; ++gi) {
+            const uint64_t gb = (base + ibase[gi]) >> S;
+            blk[gi] = (uint32_t)(gb < a.nblocks ? gb : a.nblocks - 1);
+            cf[gi] = gb < a.nblocks ? sa.coef : 0.f;
         }
+        const uint64_t gh = (uint64_t)tile * 1024u + wave * 64u + 2u * col + h; // this lane's 32-bit word of a message
+        const bool live = gh < 2 * a.W;
+        const uint32_t *const wp = words + (live ? gh : 0);
+        auto word_of = [&](uint32_t m) -> uint32_t { // m clamped: the value of a worker past the last one is never used
+            const uint32_t mc = m < sa.M ? m : sa.M - 1u;
+            const uint32_t w = wp[2 * (uint64_t)mc * a.W];
+            return live ? w : 0u;
+        };
+        auto coef_of = [&](uint32_t m, int gi) -> float {
+            const uint32_t mc = m < sa.M ? m : sa.M - 1u;
+            return sa.scales_up[(uint64_t)mc * a.nblocks + blk[gi]];
+        };
+        // stages 1 and 2 of worker m into exchange buffer m & 1, and that worker's eps table
+        auto front = [&](uint32_t m, uint32_t w) {
+            uint32_t *const epsm = tables + (m & 1u) * kMfEpsWords;
+            if (t < 256u) {
+                const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, m };
+                uint32_t e4[4];
+                philox((uint32_t)(base >> 7) + t, key_eps, e4);
+                *reinterpret_cast<uint4 *>(epsm + mf_eps_pos(4u * t)) = make_uint4(e4[0], e4[1], e4[2], e4[3]);
+            }
+            mf_front(w, k, xb + (m & 1u) * kMfXBytes, xw);
+        };
+
+        mf_v16f acc[2];
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[gi][r] = 0.f;
+
+        uint32_t wnext = word_of(1);
+        float cl[2] = { coef_of(0, 0), coef_of(0, 1) };
+        front(0, word_of(0));
+        __syncthreads();
+        for (uint32_t m = 0; m < sa.M; ++m) {
+            const uint32_t *const epsm = tables + (m & 1u) * kMfEpsWords;
+            const char *const xm = xb + (m & 1u) * kMfXBytes;
+            // worker m's eps words of this lane's groups (published by the last barrier): b5 = 0 and 1 side by side
+            uint2 ew[2];
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) ew[gi] = *reinterpret_cast<const uint2 *>(epsm + mf_eps_pos(ibase[gi] >> 5));
+            const float c[2] = { cl[0] * cf[0], cl[1] * cf[1] };
+            const uint32_t wnn = word_of(m + 2);
+            cl[0] = coef_of(m + 1, 0);
+            cl[1] = coef_of(m + 1, 1);
+            if (m + 1 < sa.M) front(m + 1, wnext);
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) {
+                mf_v16f d = mf_back(k, xm, xr + gi * 64u);
+                d[0] -= dcoff[gi];
+                const uint32_t cb = __float_as_uint(c[gi]);
+                const uint32_t e0 = ew[gi].x >> esh, e1 = ew[gi].y >> esh;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    // eps bit (b1, b2) = r & 3, b4 = (r >> 2) & 1 of word b5 = r >> 3, moved to bit 31 and xored into the
+                    // coefficient
+                    const uint32_t sc = __builtin_amdgcn_bitop3_b32(cb, ((r >> 3) ? e1 : e0) << (31 - (2 * (r & 3) + 16 * ((r >> 2) & 1))),
+                                                                    0x80000000u, 0x78);
+                    acc[gi][r] = fmaf(d[r], __uint_as_float(sc), acc[gi][r]);
+                }
+            }
+            wnext = wnn;
+            __syncthreads(); // worker m + 1 is published; everybody is done reading worker m
+        }
+
+        // The mean of the tile, natural order.  Through LDS (the exchange buffers are free now), so that a wave stores
+        // 1 KiB rows: coordinate i sits at word i + 4 (i >> 11) (the lanes of a half wave differ in b0 and b11..b14).
+        float *const tb = reinterpret_cast<float *>(lds);
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi) {
+            float *const tl = tb + ibase[gi] + 4u * (col >> 1); // the register part of i adds bits 1, 2, 4, 5 only
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tl[((r & 3) << 1) | (((r >> 2) & 1) << 4) | ((r >> 3) << 5)] = acc[gi][r];
+        }
+        __syncthreads();
+        float *const gq = static_cast<float *>(const_cast<void *>(a.src)) + base;
+        const uint64_t room = a.len_in > base ? a.len_in - base : 0; // a multiple of 64
+        const float *const tr = tb + 4u * t + 4u * ((4u * t) >> 11); // i = 4 t + 4096 q sits at this + (4096 + 8) q
+#pragma unroll
+        for (int q = 0; q < 8; ++q)
+            if (4u * t + 4096u * q < room)
+                *reinterpret_cast<float4 *>(gq + 4u * t + 4096u * q) = *reinterpret_cast<const float4 *>(tr + (4096 + 8) * q);
+        __syncthreads(); // the next tile's first worker overwrites the buffers
     }
 }
 

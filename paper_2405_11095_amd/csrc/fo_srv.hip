@@ -79,11 +79,9 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         sa.enc.src = gbar;
         sa.bits_up = bits_up; sa.scales_up = scales_up; sa.M = M;
         sa.coef = 2.f * mean_coef; // the decode side carries half values
-        const dim3 mgrid((unsigned)pl->ntiles, 1), mblock(kThreads);
-        if (pl->S == 10) FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<10>, mgrid, mblock, st, sa));
-        else if (pl->S == 12) FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<12>, mgrid, mblock, st, sa));
-        else if (pl->S == 14) FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<14>, mgrid, mblock, st, sa));
-        else FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_tile<0>, mgrid, mblock, st, sa));
+        // one workgroup fills a compute unit (its two exchange buffers take most of the LDS) and walks over tiles
+        const unsigned nwg = (unsigned)(pl->ntiles < pl->num_cus ? pl->ntiles : pl->num_cus);
+        FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_mfma, dim3(nwg), dim3(kMfThreads), st, sa, (uint32_t)pl->ntiles));
         return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
                              nullptr, 0, st);
     }
