@@ -338,6 +338,8 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
             } else if (gb < a.nblocks) {
                 l = a.scales[slot * a.scales_stride + gb];
             }
+            // the plain sign quantiser compares in the integer domain and wants -128 / (lambda sqrt(b) 2^-24) (see below)
+            if constexpr (OUT == OUT_PACK && DITHER && !MULTIK && !STATS) l = -128.f / (l * (a.sqrtb * 5.9604644775390625e-08f));
             lam[t] = l;
         }
     }
@@ -472,6 +474,43 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
             for (int p = 0; p < 8; ++p)
                 if ((uint32_t)p < a.planes) dst[(uint64_t)p * a.W] = ((uint64_t)hi[p] << 32) | lo[p];
         }
+    } else if constexpr (OUT == OUT_PACK && DITHER && !STATS) {
+        // Def. 3.2 with the dither u = (2 r + 1 - 2^24) 2^-24, r the top 24 bits of the 32-bit draw w:
+        //   z + lambda' u >= 0  <=>  r >= ((2^24 - 1) - z 2^24 / lambda') / 2  <=>  w >= T,  T = 2^31 - 128 - 128 z 2^24 / lambda',
+        // so a coordinate costs one multiply-add, one saturating conversion (T <= 0 -> 0: always +1; T >= 2^32 -> 2^32 - 1)
+        // and one integer compare.  T is rounded to 256 (1 in r), i.e. the threshold moves by at most lambda' 2^-24, a
+        // hundred times below the near-tie margin.  A NaN amplitude gives all bits 0, as NaN comparisons do.
+        uint32_t my_lo = 0u, my_hi = 0u;
+        static_for<16>([&](auto gc) {
+            constexpr int g = decltype(gc)::value;
+            uint32_t w[4];
+            const uint32_t lg = local_of(2 * g); // b6 = b7 = 0
+            philox((uint32_t)(((base + lg) >> 8) << 6) | lane, key_dit, w);
+            float kq_g = 0.f;
+            if constexpr (!SMALLB) kq_g = lam[lg >> S];
+            uint64_t word[4];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const int r = 2 * g + (s & 1) + 32 * (s >> 1); // slot s = b6 | b7 << 1
+                float kq = kq_g;
+                if constexpr (SMALLB) kq = lam[local_of(r) >> S];
+                uint32_t thr;
+                asm("v_cvt_u32_f32 %0, %1" : "=v"(thr) : "v"(fmaf(v[r], kq, 2147483520.f)));
+                word[s] = __ballot(w[s] >= thr) & __ballot(kq == kq);
+            }
+            // the 64-bit word of register r goes to lane r: one write into that lane per half
+            static_for<4>([&](auto sc) {
+                constexpr int s = decltype(sc)::value;
+                constexpr int r = 2 * g + (s & 1) + 32 * (s >> 1);
+                my_lo = write_lane<r>(my_lo, (uint32_t)word[s]);
+                my_hi = write_lane<r>(my_hi, (uint32_t)(word[s] >> 32));
+            });
+        });
+        // lane j holds the word of register j
+        const uint64_t gw = (uint64_t)tile * 512u +
+                            ((lane & 1u) | ((lane >> 5) << 1) | (((lane >> 1) & 1u) << 2) | (wave << 3) | (((lane >> 2) & 7u) << 6));
+        if (gw < a.W)
+            static_cast<uint64_t *>(a.dst)[slot * a.dst_stride + gw] = ((uint64_t)my_hi << 32) | my_lo;
     } else if constexpr (OUT == OUT_PACK) {
         uint32_t my_lo = 0u, my_hi = 0u;
         const float tscale = a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m * 2^-24 with m odd
