@@ -155,7 +155,8 @@ def main():
         "k_strided<ENC_FIRST>": M * (4 * d + 4 * n),
         # with blocks of 2^16 the workers' encode is one pass (k_contig_pair); only the server re-encodes in two
         "k_contig<IN_F32,OUT_PACK>": n_low * (4 * n + W8),
-        "k_contig_pair": M * (4 * d + W8),
+        # blocks of 2^16: the server's re-encode of the mean is one more vector through the pair kernel
+        "k_contig_pair": M * (4 * d + W8) + ((4 * n + W8) if "k_mean_mfma" in per_kernel else 0),
         "k_declow": n_dlow * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if ind else 8 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,

@@ -128,13 +128,96 @@ __device__ __forceinline__ void mf_front(uint32_t w, const MfConst &k, char *xbu
 
 // Stage 3 for one row group: reads this lane's two 16-byte pieces at xr (bytes) and returns the sixteen half values
 // (H^T q)_i / 2 (+ 2^(S-1) on the first coordinate of every block), i as given in the header comment.
-__device__ __forceinline__ mf_v16f mf_back(const MfConst &k, const char *xbuf, uint32_t xr)
+__device__ __forceinline__ mf_v16f mf_back(const mf_v8h (&b3)[2], const char *xbuf, uint32_t xr)
 {
     const mf_v8h a0 = __builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(xbuf + xr));
     const mf_v8h a1 = __builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(xbuf + xr + 32u));
     mf_v16f z = { 0 };
-    mf_v16f d = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, k.b3[0], z, 0, 0, 0);
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, k.b3[1], d, 0, 0, 0);
+    mf_v16f d = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, b3[0], z, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, b3[1], d, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Transforms of exactly 2^16 points (a block of two tiles): split (b0..b5 | b6..b10 | b11..b15), all three stages
+// full Hadamard products.  Two workgroups share a block: both run stages 1 and 2 on all 32 slabs (the packed
+// signs are small, reading and transforming them twice is cheap), but workgroup q keeps only the columns
+// b10 = q, so each holds 2^15 accumulators, as for a single tile.  Wave w handles the slabs b11..b15 = 2w, 2w + 1
+// and pairs them in one dword, so that the stage-3 contraction index (the slab) is contiguous in LDS.
+// After stage 3 lane (j, h) holds in register r of column group g = (b5 | b6..b9) the coordinate
+//   b0..b4 = 8 (r / 4) + 4 h + r % 4, b5 = g / 16, b6..b9 = g % 16, b10 = q, b11..b15 = j:
+// sixteen values of one eps word.
+// ---------------------------------------------------------------------------------------------
+constexpr uint32_t kMf16EpsWords = 32u * 36u; // eps words of one workgroup's half block: 32 per slab, padded to 36
+__device__ __forceinline__ uint32_t mf16_eps_pos(uint32_t low5, uint32_t slab) { return low5 + 36u * slab; }
+
+struct MfConst16 {
+    uint32_t b1[4];
+    uint32_t b1flip;
+    mf_v8h b2[2];
+    mf_v8h b3[2];
+};
+
+__device__ __forceinline__ void mf16_build_constants(MfConst16 &k, uint32_t lane, uint32_t wave)
+{
+    const uint32_t col = lane & 31u, hb = lane >> 5;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        const uint32_t mag = q == 0 ? 4u : q == 1 ? 2u : 1u;
+        uint32_t d = 0;
+#pragma unroll
+        for (int nib = 0; nib < 8; ++nib) d |= (mag | (parity32((4u * nib + q) & col) << 3)) << (4 * nib);
+        k.b1[q] = d;
+    }
+    k.b1flip = hb ? 0x88888888u : 0u;
+#pragma unroll
+    for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t g = 8u * (2u * mm + (e >> 2)) + 4u * hb + (e & 3u);
+            k.b2[mm][e] = (_Float16)(parity32(g & col) ? -1.f : 1.f);
+        }
+    // stage 3: k = slab in the order the exchange buffer delivers it to this wave (dwords swizzled by f), column = slab'
+    const uint32_t f = (wave & 7u) >> 1;
+#pragma unroll
+    for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t sg = 2u * ((4u * (2u * mm + hb) + (e >> 1)) ^ f) + (e & 1u);
+            k.b3[mm][e] = (_Float16)(parity32(sg & col) ? -1.f : 1.f);
+        }
+}
+
+// Stages 1 and 2 of this wave's two slabs (packed words w0, w1 of this lane) and the write into the exchange buffer:
+// row b0..b4, column group (b5 | b6..b9), dword = wave (swizzled by the column group), halves = the two slabs.
+// keep: this lane's column b6..b10 belongs to the workgroup's half (b10 = q).
+__device__ __forceinline__ void mf16_front(uint32_t w0, uint32_t w1, const MfConst16 &k, char *xbuf, uint32_t xw, bool keep)
+{
+    const mf_v16f z = { 0 };
+    const uint32_t ws[2] = { w0, w1 };
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const uint32_t f = m ? k.b1flip : 0u;
+        const mf_v8i b = { (int)(k.b1[0] ^ f), (int)(k.b1[1] ^ f), (int)(k.b1[2] ^ f), (int)(k.b1[3] ^ f), 0, 0, 0, 0 };
+        mf_v16f e[2];
+#pragma unroll
+        for (int sl = 0; sl < 2; ++sl) {
+            const uint32_t w = ws[sl];
+            const mf_v8i a = { (int)(w & 0x11111111u), (int)(w & 0x22222222u), (int)(w & 0x44444444u), (int)((w >> 1) & 0x44444444u), 0, 0, 0, 0 };
+            const mf_v16f d1 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, z, 4, 4, 0, 127, 0, 127);
+            uint32_t pk[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) pk[u] = mf_pack(d1[2 * u], d1[2 * u + 1]);
+            const mf_v8h p0 = __builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(&pk[0]));
+            const mf_v8h p1 = __builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(&pk[4]));
+            e[sl] = __builtin_amdgcn_mfma_f32_32x32x16_f16(p0, k.b2[0], z, 0, 0, 0);
+            e[sl] = __builtin_amdgcn_mfma_f32_32x32x16_f16(p1, k.b2[1], e[sl], 0, 0, 0);
+        }
+        if (keep) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) // row b0..b4 = 8 (r / 4) + 4 h + r % 4 (lane part in xw); column group + 16 m
+                *reinterpret_cast<uint32_t *>(xbuf + xw + (8u * (r >> 2) + (r & 3u)) * kMfRowBytes + 16u * 64u * m) = mf_pack(e[0][r], e[1][r]);
+        }
+    }
 }
 
 } // namespace fo

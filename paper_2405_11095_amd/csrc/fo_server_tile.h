@@ -121,7 +121,7 @@ static __global__ __launch_bounds__(kMfThreads) void k_mean_mfma(const ServerTil
             if (m + 1 < sa.M) front(m + 1, wnext);
 #pragma unroll
             for (int gi = 0; gi < 2; ++gi) {
-                mf_v16f d = mf_back(k, xm, xr + gi * 64u);
+                mf_v16f d = mf_back(k.b3, xm, xr + gi * 64u);
                 d[0] -= dcoff[gi];
                 const uint32_t cb = __float_as_uint(c[gi]);
                 const uint32_t e0 = ew[gi].x >> esh, e1 = ew[gi].y >> esh;
@@ -156,6 +156,119 @@ static __global__ __launch_bounds__(kMfThreads) void k_mean_mfma(const ServerTil
             if (4u * t + 4096u * q < room)
                 *reinterpret_cast<float4 *>(gq + 4u * t + 4096u * q) = *reinterpret_cast<const float4 *>(tr + (4096 + 8) * q);
         __syncthreads(); // the next tile's first worker overwrites the buffers
+    }
+}
+
+// The same mean for transforms of exactly 2^16 points (blocks of two tiles), one pass over the packed signs: unit
+// u = 2 block + q, workgroup q of a block keeps the columns b10 = q (see fo_mfma.h).  One amplitude per worker and
+// block.  The mean goes to memory in 4 KiB pieces (1024 consecutive coordinates per slab).
+static __global__ __launch_bounds__(kMfThreads) void k_mean_mfma_pair(const ServerTileArgs sa, const uint32_t nunits)
+{
+    __shared__ uint32_t lds[2 * kMfXWords + 2 * kMf16EpsWords];
+    static_assert(2 * kMfXWords >= 32 * 1028, "the output transposition reuses the exchange buffers");
+    char *const xb = reinterpret_cast<char *>(lds);
+    uint32_t *const tables = lds + 2 * kMfXWords;
+    const ContigArgs &a = sa.enc;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t col = lane & 31u, h = lane >> 5;
+    uint32_t rk1, rlo;
+    resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
+
+    MfConst16 k;
+    mf16_build_constants(k, lane, wave);
+
+    // exchange addresses (bytes): write row b0..b4 = 4 h (+ register part), column group b6..b9 = col % 16 (+ 16 b5),
+    // dword = wave swizzled by the column group; read row = col, column group 2 wave + gi, 16-byte piece h (and 2 + h)
+    const uint32_t xw = 4u * h * kMfRowBytes + (col & 15u) * 64u + 4u * (wave ^ ((col & 15u) >> 2));
+    const uint32_t xr = col * kMfRowBytes + 2u * wave * 64u + 16u * h;
+    const uint32_t *const words = reinterpret_cast<const uint32_t *>(sa.bits_up);
+    // eps word (b5 | b6..b9 | slab) of this lane's two column groups inside the workgroup's table
+    uint32_t epos[2];
+#pragma unroll
+    for (int gi = 0; gi < 2; ++gi) {
+        const uint32_t g = 2u * wave + gi;
+        epos[gi] = mf16_eps_pos((g >> 4) | ((g & 15u) << 1), col);
+    }
+
+    for (uint32_t unit = blockIdx.x; unit < nunits; unit += gridDim.x) {
+        const uint32_t block = unit >> 1, q = unit & 1u;
+        const uint64_t base = (uint64_t)block << 16;
+        const bool keep = (col >> 4) == q;
+        // this lane's 32-bit words of a message: slabs 2 wave and 2 wave + 1
+        const uint32_t *const wp = words + (uint64_t)block * 2048u + (2u * wave) * 64u + 2u * col + h;
+        auto word_of = [&](uint32_t m, int sl) -> uint32_t { // m clamped: a worker past the last one is never used
+            const uint32_t mc = m < sa.M ? m : sa.M - 1u;
+            return wp[2 * (uint64_t)mc * a.W + 64u * sl];
+        };
+        auto coef_of = [&](uint32_t m) -> float {
+            const uint32_t mc = m < sa.M ? m : sa.M - 1u;
+            return sa.scales_up[(uint64_t)mc * a.nblocks + block] * sa.coef;
+        };
+        auto front = [&](uint32_t m, uint32_t w0, uint32_t w1) {
+            uint32_t *const epsm = tables + (m & 1u) * kMf16EpsWords;
+            if (t < 256u) {
+                // generator block (b7..b9 | b10 = q | slab) of the block's 2048 eps words: four words (b5, b6)
+                const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, m };
+                uint32_t e4[4];
+                philox((uint32_t)(base >> 7) + ((t & 7u) | (q << 3) | ((t >> 3) << 4)), key_eps, e4);
+                *reinterpret_cast<uint4 *>(epsm + mf16_eps_pos(4u * (t & 7u), t >> 3)) = make_uint4(e4[0], e4[1], e4[2], e4[3]);
+            }
+            mf16_front(w0, w1, k, xb + (m & 1u) * kMfXBytes, xw, keep);
+        };
+        const float dcoff = (unit & 1u) == 0u && t == 0u ? 32768.f : 0.f; // first coordinate of the block: group 0 of wave 0
+
+        mf_v16f acc[2];
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[gi][r] = 0.f;
+
+        uint32_t wn0 = word_of(1, 0), wn1 = word_of(1, 1);
+        float cl = coef_of(0);
+        front(0, word_of(0, 0), word_of(0, 1));
+        __syncthreads();
+        for (uint32_t m = 0; m < sa.M; ++m) {
+            const uint32_t *const epsm = tables + (m & 1u) * kMf16EpsWords;
+            const char *const xm = xb + (m & 1u) * kMfXBytes;
+            const uint32_t ew[2] = { epsm[epos[0]] >> (4u * h), epsm[epos[1]] >> (4u * h) };
+            const uint32_t cb = __float_as_uint(cl);
+            const uint32_t wnn0 = word_of(m + 2, 0), wnn1 = word_of(m + 2, 1);
+            cl = coef_of(m + 1);
+            if (m + 1 < sa.M) front(m + 1, wn0, wn1);
+#pragma unroll
+            for (int gi = 0; gi < 2; ++gi) {
+                mf_v16f d = mf_back(k.b3, xm, xr + gi * 64u);
+                if (gi == 0) d[0] -= dcoff;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    // eps bit b0..b4 = 8 (r / 4) + 4 h + r % 4, moved to bit 31 and xored into the coefficient
+                    const uint32_t sc = __builtin_amdgcn_bitop3_b32(cb, ew[gi] << (31 - (8 * (r >> 2) + (r & 3))), 0x80000000u, 0x78);
+                    acc[gi][r] = fmaf(d[r], __uint_as_float(sc), acc[gi][r]);
+                }
+            }
+            wn0 = wnn0;
+            wn1 = wnn1;
+            __syncthreads(); // worker m + 1 is published; everybody is done reading worker m
+        }
+
+        // The workgroup's half of the mean: 1024 consecutive coordinates (b0..b9) per slab, through LDS (the exchange
+        // buffers are free now) at word 1028 slab + (b0..b9), so that a wave stores 1 KiB rows.
+        float *const tb = reinterpret_cast<float *>(lds);
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi) {
+            const uint32_t g = 2u * wave + gi;
+            float *const tl = tb + 1028u * col + 4u * h + ((g >> 4) << 5) + ((g & 15u) << 6);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) tl[8 * (r >> 2) + (r & 3)] = acc[gi][r];
+        }
+        __syncthreads();
+        float *const gq = static_cast<float *>(const_cast<void *>(a.src)) + base + (q << 10);
+#pragma unroll
+        for (int q8 = 0; q8 < 8; ++q8) { // slab (t / 256) + 4 q8, coordinates 4 (t % 256) .. + 3
+            const uint32_t slab = (t >> 8) + 4u * q8;
+            *reinterpret_cast<float4 *>(gq + 2048u * slab + 4u * (t & 255u)) = *reinterpret_cast<const float4 *>(tb + 1028u * slab + 4u * (t & 255u));
+        }
+        __syncthreads(); // the next unit's first worker overwrites the buffers
     }
 }
 

@@ -85,6 +85,21 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
                              nullptr, 0, st);
     }
+    if (pl->logb == 16) {
+        // blocks of exactly two tiles: the mean in one pass over the packed signs, two workgroups per block, then the
+        // one-pass encode of blocks of that length
+        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
+        ServerTileArgs sa;
+        sa.enc = contig_base(pl, r);
+        sa.enc.src = gbar;
+        sa.bits_up = bits_up; sa.scales_up = scales_up; sa.M = M;
+        sa.coef = 2.f * mean_coef; // the decode side carries half values
+        const uint32_t nunits = (uint32_t)(2 * pl->nblocks);
+        const unsigned nwg = nunits < pl->num_cus ? nunits : pl->num_cus;
+        FO_TRY(launch(pl, KID_SERVER_TILE, k_mean_mfma_pair, dim3(nwg), dim3(kMfThreads), st, sa, nunits));
+        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
+                             pl->buf_a, 0, st);
+    }
     if (pl->npass == 2) {
         // three-pass transforms: unfused (decode each worker into the mean, then a plain encode)
         float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
