@@ -119,6 +119,7 @@ int plan_geometry(const fo_params &q, fo_plan *pl)
     pl->stats = nullptr;
     pl->round_dev = nullptr;
     pl->num_cus = 256;
+    pl->pad32 = pl->pad16 = 0;
     if (q.block_log2 == 0) {
         uint32_t k = 6;
         while (((uint64_t)1 << k) < q.d) ++k;
@@ -179,8 +180,9 @@ extern "C" int fo_plan_create(const fo_params *params, fo_plan **out)
         if (cus > 0) pl->num_cus = (uint32_t)cus;
     }
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    const size_t sz_a = pl->npass ? up((size_t)q.M * pl->ntot * 4) : 0;
-    const size_t sz_b = up(pl->ntot * 4);
+    if (pl->npass == 1) { pl->pad32 = kRowPad32; pl->pad16 = kRowPad16; }
+    const size_t sz_a = pl->npass ? up((size_t)q.M * (pl->ntot + pl->ntiles * pl->pad32) * 4) : 0;
+    const size_t sz_b = up((pl->ntot + pl->ntiles * pl->pad32) * 4);
     const size_t sz_c = pl->npass == 2 ? up(pl->ntot * 4) : 0;
     const size_t sz_part = up((size_t)q.M * pl->ntiles * 4);
     const size_t sz_bu = up((size_t)q.M * pl->W * 8), sz_su = up((size_t)q.M * pl->nblocks * 4);
@@ -302,7 +304,7 @@ extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta
                                pl->scales_up + (uint64_t)m * pl->nblocks, 0, pl->buf_a, 0, st);
     } else {
         rc = launch_encode(pl, &tab, nullptr, 0, pl->p.d, M, 0, round, given, pl->bits_up, pl->W, pl->scales_up,
-                           pl->nblocks, pl->buf_a, pl->ntot, st, pl->p.eps_mode != FO_EPS_INDEPENDENT);
+                           pl->nblocks, pl->buf_a, pl->ntot + pl->ntiles * pl->pad32, st, pl->p.eps_mode != FO_EPS_INDEPENDENT);
     }
     if (rc) return rc;
     rc = launch_server(pl, pl->bits_up, pl->scales_up, round, pl->bits_down, pl->scales_down, nullptr, st);

@@ -55,6 +55,8 @@ struct ContigArgs {
     uint32_t planes;        // MULTIK: bit planes of the message, ceil(log2(K + 1)); plane p starts at word p * W
     uint32_t scales_only;   // IN_GRAD: write the blocks' amplitudes and stop (no transform)
     uint32_t tile0;         // first tile of this launch (a launch may cover a range of tiles)
+    uint32_t src_pad;       // IN_F32: tile t of the intermediate starts at t * (2^15 + src_pad) (see StridedArgs)
+    uint32_t dst_pad;       // k_declow: the same for its int16 output
     uint32_t party0;        // party id of slot 0 (slot y is party0 + y); FO_PARTY_SERVER stays as is
     uint32_t eps_party0;    // same for the eps stream
     uint32_t k0, k1, round_lo;
@@ -116,6 +118,7 @@ __device__ __forceinline__ void contig_tile(const ContigArgs &a, const PtrTab &t
                                                         : static_cast<const float *>(a.src) + slot * a.src_stride;
         // GUARDED = false: the caller vouches that the whole tile lies inside the input (no per-chunk checks)
         const uint64_t limit = (IN == IN_GRAD && GUARDED) ? a.len_in : ~0ull;
+        if constexpr (IN == IN_F32) src += (uint64_t)tile * a.src_pad;
 #pragma unroll
         for (int c = 0; c < 16; ++c) {
             const uint64_t i = base + wave * 4096u + c * 256u + lane * 4u;

@@ -44,7 +44,8 @@ int launch_decode(fo_plan *pl, const uint64_t *bits, const float *scales, uint64
     s.dst = out; s.len_out = len_out; s.store_mode = store_mode; s.out_coef = out_coef; s.delta = delta;
     s.scales = scales; s.scales_stride = 0; s.eps_party0 = eps_party_of(pl, party);
     if (pl->npass == 1 && !multik) {
-        // int16 intermediate between the two passes
+        // int16 intermediate between the two passes (padded rows when it is the plan's own buffer)
+        c.dst_pad = s.src_pad = tmp == pl->buf_a ? pl->pad16 : 0u;
         FO_TRY(launch_declow(pl, grid, st, c));
         s.src = tmp;
         FO_TRY((launch_strided<SM_DEC_LAST, true>(pl, KID_DEC_HIGH, grid, st, s, none)));

@@ -189,7 +189,7 @@ static __global__ __launch_bounds__(kThreads, 4) void k_declow(const ContigArgs 
     declow_tile<15>(src, a.W, tile, 15u, xbuf, xbuf, v);
 
     // store: a wave writes 256 contiguous bytes per register
-    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<int16_t *>(a.dst) + slot * a.dst_stride + ((uint64_t)tile << kTileLog2));
+    uint32_t *dst = reinterpret_cast<uint32_t *>(static_cast<int16_t *>(a.dst) + slot * a.dst_stride + ((uint64_t)tile << kTileLog2) + (uint64_t)tile * a.dst_pad);
     const uint32_t dt = lane | (wave << 8);
 #pragma unroll
     for (int r = 0; r < 32; ++r) dst[dt + declow_reg_dword(r)] = __builtin_bit_cast(uint32_t, v[r]);

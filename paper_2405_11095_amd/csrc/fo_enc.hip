@@ -91,6 +91,10 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
     s.src = src; s.src_stride = src_stride; s.use_tab = tab ? 1u : 0u; s.len_in = len_in;
     s.dst = (pl->npass == 2) ? pl->buf_c : tmp; s.dst_stride = (pl->npass == 2) ? 0 : tmp_stride;
     s.partials = pl->partials; s.eps_party0 = eps_party_of(pl, party0);
+    // the intermediate in plan scratch has padded rows; the one of fo_encode_noalloc and the server's (tmp == nullptr
+    // never happens here) follow the plan's setting as well
+    const uint32_t pad = pl->npass == 1 ? pl->pad32 : 0u;
+    s.dst_pad = pad;
     if (pl->npass == 2 && nslots != 1) return FO_EINVAL; // three-pass transforms are encoded one party at a time
     FO_TRY(launch_strided<SM_ENC_FIRST>(pl, KID_ENC_HIGH, grid, st, s, tb));
     if (pl->npass == 2) {
@@ -103,6 +107,7 @@ int launch_encode(fo_plan *pl, const PtrTab *tab, const float *src, uint64_t src
         if (common) FO_TRY(launch_common_scales(pl, st, scales, nslots));
     }
     c.src = tmp; c.src_stride = tmp_stride;
+    c.src_pad = pad;
     FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid, st, c, none));
     return FO_OK;
 }

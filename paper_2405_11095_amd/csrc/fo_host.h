@@ -65,6 +65,7 @@ struct fo_plan {
     uint32_t hb[2];      // stages of each strided pass (pass 0 is adjacent to the contiguous tile)
     uint32_t planes;     // bit planes of the downlink message: ceil(log2(K + 1))
     uint32_t num_cus;    // compute units of the device the plan was made on
+    uint32_t pad32, pad16; // elements between the 2^15-element rows of the fp32 / int16 intermediates (two-pass transforms)
     float coef_lambda, sqrtb, rsqrtb, coef_s;
     float coef_lambda_s; // alpha_s sqrt(ln b / b): measured-norm rule for the server
     // scratch (device)
@@ -237,6 +238,9 @@ inline uint32_t eps_party_of(const fo_plan *pl, uint32_t party)
 // ---------------------------------------------------------------------------------------------
 // Launch sequences (one translation unit each)
 // ---------------------------------------------------------------------------------------------
+
+// Row padding of the intermediates of two-pass transforms: one 128-byte line (see StridedArgs).
+constexpr uint32_t kRowPad32 = 32, kRowPad16 = 64;
 
 // fo_api.hip: the small amplitude kernels
 int launch_finalize_scales(fo_plan *pl, hipStream_t st, uint32_t nslots, float coef, float *scales, uint64_t scales_stride);

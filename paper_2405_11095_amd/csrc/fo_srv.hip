@@ -60,11 +60,12 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.gbar = gbar_or_null;
         s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
         s.partials = l2s ? pl->partials : nullptr;
+        s.dst_pad = pl->pad32;
         FO_TRY(launch_strided<SM_SHARED>(pl, KID_SERVER_HIGH, grid1, st, s, none));
         if (zero_transform) return FO_OK;
         if (l2s) FO_TRY(finalize_server_scales());
         ContigArgs e = contig_base(pl, r);
-        e.src = pl->buf_b; e.dst = bits_down;
+        e.src = pl->buf_b; e.dst = bits_down; e.src_pad = pl->pad32;
         e.scales = scales_down;
         e.party0 = FO_PARTY_SERVER; e.eps_party0 = FO_PARTY_SERVER;
         set_quantiser(e, pl, FO_PARTY_SERVER);
@@ -116,13 +117,13 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
     {
         ContigArgs c = contig_base(pl, r);
         c.src = bits_up; c.src_stride = pl->W;
-        c.dst = pl->buf_a; c.dst_stride = pl->ntot;
+        c.dst = pl->buf_a; c.dst_stride = pl->ntot + pl->ntiles * pl->pad16; c.dst_pad = pl->pad16;
         FO_TRY(launch_declow(pl, dim3((unsigned)pl->ntiles, M), st, c));
     }
     {
         StridedArgs s = strided_base(pl, r, 0);
-        s.src = pl->buf_a; s.src_stride = pl->ntot;
-        s.dst = pl->buf_b;
+        s.src = pl->buf_a; s.src_stride = pl->ntot + pl->ntiles * pl->pad16; s.src_pad = pl->pad16;
+        s.dst = pl->buf_b; s.dst_pad = pl->pad32;
         s.scales = scales_up; s.scales_stride = pl->nblocks;
         s.gbar = gbar_or_null;
         s.M = M; s.out_coef = 2.f * mean_coef; s.eps_party0 = FO_PARTY_SERVER; // int16 input holds half values
@@ -132,7 +133,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
     }
     {
         ContigArgs c = contig_base(pl, r);
-        c.src = pl->buf_b; c.src_stride = 0;
+        c.src = pl->buf_b; c.src_stride = 0; c.src_pad = pl->pad32;
         c.dst = bits_down; c.dst_stride = 0;
         c.scales = scales_down; c.scales_stride = 0;
         c.party0 = FO_PARTY_SERVER; c.eps_party0 = FO_PARTY_SERVER;

@@ -48,6 +48,10 @@ struct StridedArgs {
     const unsigned long long *round_dev; // optional: round counter read at run time
     float out_coef;        // value = lambda * out_coef * (transformed integer)
     float delta;
+    // Padding of an intermediate that the neighbouring contiguous pass reads or writes tile by tile: row R (2^ls elements)
+    // starts at R * (2^ls + pad) elements, which keeps rows that are a power of two apart off the same memory channels.
+    uint32_t dst_pad;      // ENC_FIRST, SERVER, SHARED: fp32 destination
+    uint32_t src_pad;      // DEC_LAST, SERVER with the int16 source
 };
 
 // Element offset of tile coordinate u from the tile origin.  Each bit of u has a fixed weight
@@ -285,11 +289,13 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
 
     // ---- input of one tile (layout LA) as 32 pairs
     auto load_int = [&](int32_t (&v)[kSV], const void *src_base) {
+        const uint32_t spad = IN16 ? a.src_pad : 0u;
+        const uint32_t otp = ota + (uta >> cb) * spad;
 #pragma unroll
         for (int p = 0; p < kSP; ++p) {
-            const uint32_t ro = g.off(L::pa(p)); // wave-uniform
+            const uint32_t ro = g.off(L::pa(p)) + (L::pa(p) >> cb) * spad; // wave-uniform
             if constexpr (IN16) {
-                const uint32_t d = ld_at<uint32_t>(static_cast<const int16_t *>(src_base) + ro, ota * 2u);
+                const uint32_t d = ld_at<uint32_t>(static_cast<const int16_t *>(src_base) + ro, otp * 2u);
                 v[2 * p] = (int32_t)(int16_t)(d & 0xFFFFu);
                 v[2 * p + 1] = (int32_t)d >> 16;
             } else {
@@ -349,7 +355,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
                 v[2 * p + 1] = d.y;
             }
         } else {
-            const char *src = static_cast<const char *>(a.src) + (slot * a.src_stride + g.origin) * (IN16 ? 2u : 4u);
+            const char *src = static_cast<const char *>(a.src) + (slot * a.src_stride + g.origin + (IN16 ? (g.origin >> g.ls) * a.src_pad : 0u)) * (IN16 ? 2u : 4u);
             load_int(v, src);
         }
 
@@ -387,14 +393,17 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
                 }
             }
         } else {
-            TV *dst = static_cast<TV *>(a.dst) + slot * a.dst_stride + g.origin;
+            const uint32_t pad = (MODE == SM_ENC_FIRST) ? a.dst_pad : 0u;
+            TV *dst = static_cast<TV *>(a.dst) + slot * a.dst_stride + g.origin + (g.origin >> g.ls) * pad;
+            const uint32_t ot_pad = ot_out + (ut_out >> cb) * pad;
 #pragma unroll
             for (int p = 0; p < kSP; ++p) {
                 using T2 = typename std::conditional<FIN, f32x2, i32x2>::type;
                 T2 d;
                 d.x = v[2 * p];
                 d.y = v[2 * p + 1];
-                st_uniform<T2>(dst + g.off(upair_out(p)), ot_out * 4u, d);
+                const uint32_t up = upair_out(p);
+                st_uniform<T2>(dst + g.off(up) + (up >> cb) * pad, ot_pad * 4u, d);
             }
         }
     } else {
@@ -426,10 +435,11 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
         uint32_t raw[kSP]; // packed tile of the next worker, in flight while the current one is transformed
 #pragma unroll
         for (int r = 0; r < kSV; ++r) acc[r] = 0.f;
+        const uint32_t otp = ota + (uta >> cb) * a.src_pad;
         auto request = [&](uint32_t m) {
-            const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin;
+            const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin + (g.origin >> g.ls) * a.src_pad;
 #pragma unroll
-            for (int p = 0; p < kSP; ++p) raw[p] = ld_uniform<uint32_t>(src + g.off(L::pa(p)), ota * 2u);
+            for (int p = 0; p < kSP; ++p) raw[p] = ld_uniform<uint32_t>(src + g.off(L::pa(p)) + (L::pa(p) >> cb) * a.src_pad, otp * 2u);
         };
         // finish worker m, whose packed tile is in `raw`; with PREFETCH the registers of `raw` are refilled
         // with worker m + 1 as soon as they have been unpacked
@@ -510,10 +520,11 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             else exchange<float, LV>(acc, xbuf, lane, wave);
         }
         stages_a<float, LV>(acc, cb);
-        float *dst = static_cast<float *>(a.dst) + g.origin;
+        float *dst = static_cast<float *>(a.dst) + g.origin + (g.origin >> g.ls) * a.dst_pad;
+        const uint32_t otd = ota + (uta >> cb) * a.dst_pad;
 #pragma unroll
         for (int p = 0; p < kSP; ++p)
-            ref_at<float2>(dst + g.off(L::pa(p)), ota * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
+            ref_at<float2>(dst + g.off(L::pa(p)) + (L::pa(p) >> cb) * a.dst_pad, otd * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
     }
 }
 
