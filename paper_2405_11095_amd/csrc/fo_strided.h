@@ -237,6 +237,66 @@ __device__ __forceinline__ void flip_pair(float &x0, float &x1, uint32_t wshift)
     x1 = __uint_as_float(__float_as_uint(x1) ^ ((wshift << 30) & 0x80000000u));
 }
 
+// Tail of the server passes, on the mean of one tile held in layout LB (LA if no row bit lives in the wave index):
+// optional copy of the mean, the tile's sum of squares for the measured-norm amplitude, eps^s flip, the forward
+// stages of the re-encode in reverse layout order, store of the fp32 intermediate (Sec. 4, server-to-workers encoding).
+// All threads of the workgroup call it; xbuf (kTile words if WIDE, else kXWords) and epsw (kEpsWords) are free on entry.
+template <int LV, bool WIDE>
+__device__ __forceinline__ void server_reencode(float (&acc)[1 << LV], const StridedArgs &a, const StridedGeom &g, uint32_t tile,
+                                                uint32_t rk1, uint32_t rlo, uint32_t *xbuf, uint32_t *epsw, float *red, bool need_x)
+{
+    using L = SL<LV>;
+    constexpr int kSV = L::V, kSP = L::P;
+    const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
+    const uint32_t cb = g.cb;
+    const uint32_t uta = L::ta(lane, wave), utb = L::tb(lane, wave);
+    const uint32_t ota = g.off(uta), otb = g.off(utb);
+    const uint32_t ut_out = need_x ? utb : uta, ot_out = need_x ? otb : ota;
+    auto upair_out = [&](int p) -> uint32_t { return need_x ? L::pb(p) : L::pa(p); };
+    const uint32_t eshift = (lane & 15u) << 1;
+    if (a.gbar) {
+        float *gq = a.gbar + g.origin;
+#pragma unroll
+        for (int p = 0; p < kSP; ++p)
+            ref_at<float2>(gq + g.off(upair_out(p)), ot_out * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
+    }
+    // measured-norm server amplitude: this tile's sum of squares of the mean (the eps flip does not change it)
+    if (a.partials) {
+        float ss = 0.f;
+#pragma unroll
+        for (int r = 0; r < kSV; r += 4)
+            ss += (acc[r] * acc[r] + acc[r + 1] * acc[r + 1]) + (acc[r + 2] * acc[r + 2] + acc[r + 3] * acc[r + 3]);
+        ss = wave_sum(ss, 6);
+        __syncthreads(); // red is free
+        if (lane == 0) red[wave] = ss;
+        __syncthreads();
+        if (t == 0) {
+            float tot = 0.f;
+            for (int w = 0; w < L::T / 64; ++w) tot += red[w];
+            a.partials[tile] = tot;
+        }
+    }
+    // re-encode: eps^s flip, then the same stages in reverse layout order
+    const RngKey key_s = { a.k0, rk1, kDomainEps, rlo, a.eps_party0 };
+    __syncthreads();
+    fill_eps<L::T>(epsw, g, key_s, t);
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < kSP; ++p)
+        flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
+    if (need_x) {
+        stages_b<float, LV>(acc, cb);
+        if constexpr (WIDE) exchange_wide<float, LV>(acc, xbuf, lane, wave);
+        else exchange<float, LV>(acc, xbuf, lane, wave);
+    }
+    stages_a<float, LV>(acc, cb);
+    float *dst = static_cast<float *>(a.dst) + g.origin + (g.origin >> g.ls) * a.dst_pad;
+    const uint32_t otd = ota + (uta >> cb) * a.dst_pad;
+#pragma unroll
+    for (int p = 0; p < kSP; ++p)
+        ref_at<float2>(dst + g.off(L::pa(p)) + (L::pa(p) >> cb) * a.dst_pad, otd * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
+}
+
 // HB = 0: the number of stages and the row stride are read from the arguments.  HB > 0: compiled
 // for exactly HB stages with rows 2^15 apart (the pass next to the contiguous tile), which turns
 // every per-register offset into a constant and removes the stage-selection branches.
@@ -484,47 +544,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
         }
         process(a.M - 1, std::false_type{});
         }
-        if (a.gbar) {
-            float *gq = a.gbar + g.origin;
-#pragma unroll
-            for (int p = 0; p < kSP; ++p)
-                ref_at<float2>(gq + g.off(upair_out(p)), ot_out * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
-        }
-        // measured-norm server amplitude: this tile's sum of squares of the mean (the eps flip does not change it)
-        if (a.partials) {
-            float ss = 0.f;
-#pragma unroll
-            for (int r = 0; r < kSV; r += 4)
-                ss += (acc[r] * acc[r] + acc[r + 1] * acc[r + 1]) + (acc[r + 2] * acc[r + 2] + acc[r + 3] * acc[r + 3]);
-            ss = wave_sum(ss, 6);
-            __syncthreads(); // red is free
-            if (lane == 0) red[wave] = ss;
-            __syncthreads();
-            if (t == 0) {
-                float tot = 0.f;
-                for (int w = 0; w < L::T / 64; ++w) tot += red[w];
-                a.partials[tile] = tot;
-            }
-        }
-        // re-encode: eps^s flip, then the same stages in reverse layout order
-        const RngKey key_s = { a.k0, rk1, kDomainEps, rlo, a.eps_party0 };
-        __syncthreads();
-        fill_eps<L::T>(epsw, g, key_s, t);
-        __syncthreads();
-#pragma unroll
-        for (int p = 0; p < kSP; ++p)
-            flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
-        if (need_x) {
-            stages_b<float, LV>(acc, cb);
-            if constexpr (WIDE) exchange_wide<float, LV>(acc, xbuf, lane, wave);
-            else exchange<float, LV>(acc, xbuf, lane, wave);
-        }
-        stages_a<float, LV>(acc, cb);
-        float *dst = static_cast<float *>(a.dst) + g.origin + (g.origin >> g.ls) * a.dst_pad;
-        const uint32_t otd = ota + (uta >> cb) * a.dst_pad;
-#pragma unroll
-        for (int p = 0; p < kSP; ++p)
-            ref_at<float2>(dst + g.off(L::pa(p)) + (L::pa(p) >> cb) * a.dst_pad, otd * 4u) = make_float2(acc[2 * p], acc[2 * p + 1]);
+        server_reencode<LV, WIDE>(acc, a, g, tile, rk1, rlo, xbuf, epsw, red, need_x);
     }
 }
 

@@ -46,6 +46,10 @@ CASES = [
     ("blocked_b65536_lower_ragged", (1 << 17) + 9_999, 2, 16, "gaussian"),
     # the benchmark's geometry (n = 2^25: ten strided stages, the specialised kernels), fewer workers
     ("c3_geometry_n2p25", 25_557_032, 3, 0, "heavy"),
+    # the same geometry with one worker (no prefetch of a next worker in the server pass), and two blocks of 2^25
+    # (server tiles of the second block start 2^25 coordinates up), the second partly filled
+    ("n2p25_single_worker", (1 << 24) + 1, 1, 0, "gaussian"),
+    ("blocked_b2p25_two_blocks", (1 << 25) + 300_001, 2, 25, "gaussian"),
 ]
 
 
