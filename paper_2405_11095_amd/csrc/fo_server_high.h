@@ -14,12 +14,13 @@
 //   stage A (rA -> tA): x = 128 (x >> 7) + (x & 127).  Both pieces are made in the integer domain, two per
 //       instruction, as fp16 bit patterns whose exponent is chosen so that the significand counts in the wanted unit:
 //       0x6400 + 128 + (x >> 7) is the number 1152 + (x >> 7), 0x4800 + (x & 127) is 8 + (x & 127) / 128.
-//       Both go against 128 H_32; the biases add (1152 * 128 + 1024) * 32 to the outputs tA = 0 and nothing
-//       elsewhere (every other column of H_32 sums to zero).
-//   stage B (rB -> tB): the stage-A result, bias removed and scaled by 2^-9 in one fma, is at most 2^10 with
-//       twenty significant bits: v_cvt_pkrtz keeps the top eleven (first piece), the remainder, exact in fp32,
-//       has at most ten (second piece).  Both go against the same 128 H_32 (one constant operand for the
-//       whole kernel); the factor 2^9 / 128 is folded into the amplitude.
+//       Both go against H_32 / 4, so the product is the transform times 2^-9 (a power of two: still exact); the
+//       biases add (1152 * 128 + 1024) * 32 / 512 to the outputs tA = 0 and nothing elsewhere (every other column
+//       of H_32 sums to zero), and the accumulator of the product starts from minus that.
+//   stage B (rB -> tB): the stage-A result is at most 2^10 with twenty significant bits: v_cvt_pkrtz keeps the
+//       top eleven (first piece), the remainder, exact in fp32, has at most ten (second piece).  Both go against
+//       the same H_32 / 4 (one constant operand for the whole kernel); the factor 2^11 is folded into the
+//       amplitude.
 // Every product and sum is an integer multiple of its unit below 2^24 units, so the result equals the
 // vector-unit kernel's bit for bit.
 //
@@ -37,7 +38,7 @@ constexpr uint32_t kShRowWords = 36u;                     // the 32 rA of one (c
 constexpr uint32_t kShPairWords = 32u * kShRowWords + 4u; // one column pair; + 4 spreads the pairs over the banks
 constexpr uint32_t kShStageWords = 16u * kShPairWords;    // one worker's tile
 constexpr uint32_t kShTransPitch = 17u;                   // 8-byte units per row of the final transposition (16 pairs + 1)
-constexpr uint32_t kShLdsWords = 2u * kShStageWords + 2u * 1024u + kRedWords;
+constexpr uint32_t kShLdsWords = 2u * kShStageWords + 2u * 1024u + kRedWords + 32u; // + the two bias vectors
 static_assert(1024u * kShTransPitch * 2u <= 2u * kShStageWords, "the transposition reuses the staging buffers");
 static_assert(kTile <= 2u * kShStageWords, "the re-encode's exchange reuses the staging buffers");
 static_assert(kShLdsWords * 4u <= 160u * 1024u, "LDS of a compute unit");
@@ -52,6 +53,7 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
     __shared__ __attribute__((aligned(16))) uint32_t lds[kShLdsWords];
     uint32_t *const epsw = lds + 2u * kShStageWords;
     float *const red = reinterpret_cast<float *>(lds + 2u * kShStageWords + 2u * 1024u);
+    float *const bias_tab = reinterpret_cast<float *>(lds + 2u * kShStageWords + 2u * 1024u + kRedWords);
 
     const uint32_t t = threadIdx.x, lane = t & 63u, wave = t >> 6;
     const uint32_t col = lane & 31u, h = lane >> 5;
@@ -66,20 +68,24 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
     g.origin = ((uint64_t)(tile >> 10) << 25) + ((uint64_t)(tile & 1023u) << 5);
     const uint64_t gb = g.origin >> a.logb;
 
-    // constant operand of all products: 128 H_32 in the k order of the operand registers
+    // constant operand of all products: H_32 / 4 in the k order of the operand registers
     mf_v8h bh[2];
 #pragma unroll
     for (int mm = 0; mm < 2; ++mm)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const uint32_t k = 8u * (2u * mm + (e >> 2)) + 4u * h + (e & 3u);
-            bh[mm][e] = (_Float16)(parity32(k & col) ? -128.f : 128.f);
+            bh[mm][e] = (_Float16)(parity32(k & col) ? -0.25f : 0.25f);
         }
     // the two constants of the second piece in registers, so that it is one v_and_or_b32
     uint32_t lo_mask = 0x007F007Fu, lo_magic = 0x48004800u;
     asm volatile("" : "+s"(lo_mask));
     asm volatile("" : "+v"(lo_magic));
-    const float neg_bias = col == 0u ? -(float)((1152 * 128 + 1024) * 32) * 0x1p-9f : 0.f;
+    // Stage A's products start from minus the bias of the pieces instead of zero: (1152 * 128 + 1024) * 32 / 512 on the
+    // lanes tA = 0, nothing elsewhere.  The two vectors live in LDS and are read into the accumulator registers, so
+    // the bias costs neither registers nor vector instructions.
+    if (t < 32u) bias_tab[t] = t < 16u ? 0.f : -(float)((1152 * 128 + 1024) * 32) * 0x1p-9f;
+    const float *const bias_mine = bias_tab + (col == 0u ? 16u : 0u);
 
     // loads: lane = (column pair, rB bits 0..1), wave = (rB bits 2..4, rA bit 4), register p = rA bits 0..3
     const uint32_t cp = lane & 15u, rl = lane >> 4;
@@ -144,11 +150,10 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
         // the next worker's eps table, while the reads above are on their way; the next barrier publishes it (its
         // buffer was last read one worker ago, before this worker's barrier)
         if constexpr (PREFETCH) fill_eps_of(m + 1);
-        const uint32_t cbits = __builtin_amdgcn_readfirstlane(__float_as_uint(lam_now * a.out_coef * 4.f));
+        const uint32_t cbits = __builtin_amdgcn_readfirstlane(__float_as_uint(lam_now * a.out_coef * 2048.f));
         // The two columns of the wave are interleaved by hand, so that the products of one column run while the
         // vector unit prepares or consumes the other: A0 | pieces 1, A1 | split 0, B0 | split 1, B1 | accumulate 0.
-        auto mfma4 = [&](const uint32_t (&p0)[8], const uint32_t (&p1)[8]) -> mf_v16f {
-            const mf_v16f z = { 0 };
+        auto mfma4 = [&](const uint32_t (&p0)[8], const uint32_t (&p1)[8], const mf_v16f &z) -> mf_v16f {
             mf_v16f d = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(&p0[0])), bh[0], z, 0, 0, 0);
             d = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(&p0[4])), bh[1], d, 0, 0, 0);
             d = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(mf_v8h, *reinterpret_cast<const uint4 *>(&p1[0])), bh[0], d, 0, 0, 0);
@@ -170,27 +175,41 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
         auto split = [&](const mf_v16f &d, uint32_t (&hp)[8], uint32_t (&lp)[8]) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const float t0 = fmaf(d[2 * i], 0x1p-9f, neg_bias), t1 = fmaf(d[2 * i + 1], 0x1p-9f, neg_bias);
-                const auto top = __builtin_amdgcn_cvt_pkrtz(t0, t1);
-                hp[i] = __builtin_bit_cast(uint32_t, top);
-                lp[i] = mf_pack(t0 - (float)top[0], t1 - (float)top[1]);
+                hp[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d[2 * i], d[2 * i + 1]));
+                // remainder = value - first piece, formed and converted in one mixed-precision fma per half
+                // (exact: at most ten significant bits)
+                uint32_t rest;
+                asm("v_fma_mixlo_f16 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(rest) : "v"(hp[i]), "v"(d[2 * i]));
+                asm("v_fma_mixhi_f16 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(rest) : "v"(hp[i]), "v"(d[2 * i + 1]));
+                lp[i] = rest;
             }
         };
+        auto bias_vec = [&]() -> mf_v16f {
+            asm volatile("" ::: "memory"); // read where it is used, not held in registers
+            mf_v16f z;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4 *>(bias_mine + 4 * q);
+                z[4 * q] = v.x; z[4 * q + 1] = v.y; z[4 * q + 2] = v.z; z[4 * q + 3] = v.w;
+            }
+            return z;
+        };
+        const mf_v16f zero = { 0 };
         uint32_t pa0[8], pb0[8], pa1[8], pb1[8];
         pieces(0, pa0, pb0);
-        const mf_v16f d0 = mfma4(pa0, pb0);
+        const mf_v16f d0 = mfma4(pa0, pb0, bias_vec());
         if constexpr (PREFETCH) request(m + 1, 0);
         __builtin_amdgcn_sched_barrier(0);
         pieces(1, pa1, pb1);
-        const mf_v16f d1 = mfma4(pa1, pb1);
+        const mf_v16f d1 = mfma4(pa1, pb1, bias_vec());
         if constexpr (PREFETCH) request(m + 1, 1);
         __builtin_amdgcn_sched_barrier(0);
         split(d0, pa0, pb0);
-        const mf_v16f e0 = mfma4(pa0, pb0);
+        const mf_v16f e0 = mfma4(pa0, pb0, zero);
         if constexpr (PREFETCH) request(m + 1, 2);
         __builtin_amdgcn_sched_barrier(0);
         split(d1, pa1, pb1);
-        const mf_v16f e1 = mfma4(pa1, pb1);
+        const mf_v16f e1 = mfma4(pa1, pb1, zero);
         if constexpr (PREFETCH) request(m + 1, 3);
         __builtin_amdgcn_sched_barrier(0);
         // register r: row 32 tA + tB with tA = 8 (r / 4) + 4 h + r % 4, tB = lane % 32; columns 2 wave, 2 wave + 1.
