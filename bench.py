@@ -159,6 +159,7 @@ def main():
         "k_contig_pair": M * (4 * d + W8) + ((4 * n + W8) if "k_mean_mfma" in per_kernel else 0),
         "k_declow": n_dlow * (W8 + 4 * n),
         "k_strided<SERVER>": (M * 4 * n + 4 * n) if ind else 8 * n,
+        "k_server_mfma": M * 4 * n + 4 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_mean_mfma": M * W8 + 4 * n,
         "k_server_tile": M * W8 + W8,
@@ -171,6 +172,7 @@ def main():
     moved = dict(model)
     moved["k_declow"] = n_dlow * (W8 + 2 * n)
     moved["k_strided<SERVER>"] = (M * 2 * n + 4 * n) if ind else 8 * n
+    moved["k_server_mfma"] = M * 2 * n + 4 * n
     moved["k_strided<DEC_LAST>"] = 2 * n + 8 * d
     step_bytes = model.get(dom)
     bytes_per_launch = step_bytes * args.steps / launches if step_bytes else None

@@ -29,6 +29,7 @@ enum KernelId {
     KID_DEC_MID,        // k_strided<MID_I32>
     KID_DEC_HIGH,       // k_strided<DEC_LAST>
     KID_SERVER_HIGH,    // k_strided<SERVER> / k_strided<SHARED>
+    KID_SERVER_MFMA,    // k_server_mfma
     KID_COUNT_LOW,      // k_contig<IN_COUNT,*>
     KID_SERVER_TILE,    // k_mean_mfma
     KID_SHALL,          // k_shall
@@ -40,7 +41,7 @@ enum KernelId {
 inline const char *const kKernelNames[KID_COUNT] = {
     "k_contig<IN_GRAD,OUT_PACK>", "k_strided<ENC_FIRST>", "k_strided<MID_F32>", "k_contig<IN_F32,OUT_PACK>",
     "k_decode_tile",  "k_declow", "k_strided<MID_I32>", "k_strided<DEC_LAST>",
-    "k_strided<SERVER>", "k_contig<IN_COUNT>", "k_mean_mfma", "k_shall", "k_contig_pair", "k_decode_pair", "scale kernels",
+    "k_strided<SERVER>", "k_server_mfma", "k_contig<IN_COUNT>", "k_mean_mfma", "k_shall", "k_contig_pair", "k_decode_pair", "scale kernels",
 };
 
 struct Profiler {
@@ -143,7 +144,7 @@ inline bool args_ok(const StridedArgs &s, const PtrTab &tab, int kid)
     if (!s.dst) return false;
     if (kid == KID_ENC_HIGH ? (s.use_tab ? !tab.p[0] : !s.src) : !s.src) return false;
     if (kid == KID_ENC_HIGH && !s.partials) return false;
-    if ((kid == KID_DEC_HIGH || kid == KID_SERVER_HIGH) && !s.scales) return false;
+    if ((kid == KID_DEC_HIGH || kid == KID_SERVER_HIGH || kid == KID_SERVER_MFMA) && !s.scales) return false;
     return s.hb >= 1 && s.hb <= 10 && s.ls >= (uint32_t)kTileLog2;
 }
 template <typename... Args>
