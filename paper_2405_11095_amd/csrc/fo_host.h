@@ -2,7 +2,7 @@
 // fo_dec.hip, fo_srv.hip): the plan, the kernel launcher with its optional event bracketing, argument-block
 // builders and the launch sequences' declarations.  The library is split into several translation units only
 // so that they compile side by side; every step of the codec runs in the kernels of fo_contig.h, fo_strided.h,
-// fo_declow.h, fo_server_tile.h and fo_shall.h.
+// fo_declow.h, fo_server_tile.h, fo_server_high.h and fo_shall.h.
 #pragma once
 #include <hip/hip_runtime.h>
 
