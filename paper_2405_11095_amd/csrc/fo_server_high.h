@@ -78,6 +78,9 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
             bh[mm][e] = (_Float16)(parity32(k & col) ? -0.25f : 0.25f);
         }
     // the two constants of the second piece in registers, so that it is one v_and_or_b32
+    // (and the -1 of stage B's remainder, so that it stays a multiply-add the compiler can emit as v_fma_mixlo/hi_f16)
+    float minus_one = -1.f;
+    asm volatile("" : "+v"(minus_one));
     uint32_t lo_mask = 0x007F007Fu, lo_magic = 0x48004800u;
     asm volatile("" : "+s"(lo_mask));
     asm volatile("" : "+v"(lo_magic));
@@ -178,10 +181,10 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
                 hp[i] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(d[2 * i], d[2 * i + 1]));
                 // remainder = value - first piece, formed and converted in one mixed-precision fma per half
                 // (exact: at most ten significant bits)
-                uint32_t rest;
-                asm("v_fma_mixlo_f16 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(rest) : "v"(hp[i]), "v"(d[2 * i]));
-                asm("v_fma_mixhi_f16 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "+v"(rest) : "v"(hp[i]), "v"(d[2 * i + 1]));
-                lp[i] = rest;
+                typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+                const h2 top = __builtin_bit_cast(h2, hp[i]);
+                const h2 rest = { (_Float16)fmaf((float)top[0], minus_one, d[2 * i]), (_Float16)fmaf((float)top[1], minus_one, d[2 * i + 1]) };
+                lp[i] = __builtin_bit_cast(uint32_t, rest);
             }
         };
         auto bias_vec = [&]() -> mf_v16f {
