@@ -1,5 +1,6 @@
 // C ABI of the FO-SGD codec (declared in include/fo.h): argument checks, plan scratch and the small amplitude
 // kernels.  The launch sequences live in fo_enc.hip, fo_dec.hip and fo_srv.hip.
+#include <cstdlib>
 #include "fo_host.h"
 
 using namespace fo;
@@ -120,6 +121,12 @@ int plan_geometry(const fo_params &q, fo_plan *pl)
     pl->round_dev = nullptr;
     pl->num_cus = 256;
     pl->pad32 = pl->pad16 = 0;
+    // FO_SERVER_VECTOR_UNIT=1 in the environment keeps the server pass of 2^25-blocks on the vector-unit kernel: the two
+    // kernels give the same bits, and the tests use the switch to show it
+    {
+        const char *e = std::getenv("FO_SERVER_VECTOR_UNIT");
+        pl->server_mfma = !(e && e[0] == '1');
+    }
     if (q.block_log2 == 0) {
         uint32_t k = 6;
         while (((uint64_t)1 << k) < q.d) ++k;

@@ -67,6 +67,7 @@ struct fo_plan {
     uint32_t planes;     // bit planes of the downlink message: ceil(log2(K + 1))
     uint32_t num_cus;    // compute units of the device the plan was made on
     uint32_t pad32, pad16; // elements between the 2^15-element rows of the fp32 / int16 intermediates (two-pass transforms)
+    bool server_mfma;    // blocks of 2^25: the server pass on the matrix cores (off: the vector-unit kernel, same results)
     float coef_lambda, sqrtb, rsqrtb, coef_s;
     float coef_lambda_s; // alpha_s sqrt(ln b / b): measured-norm rule for the server
     // scratch (device)

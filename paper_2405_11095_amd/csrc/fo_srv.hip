@@ -129,7 +129,7 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         s.gbar = gbar_or_null;
         s.M = M; s.out_coef = 2.f * mean_coef; s.eps_party0 = FO_PARTY_SERVER; // int16 input holds half values
         s.partials = l2s ? pl->partials : nullptr;
-        if (s.hb == 10) // blocks of 2^25: the inverse stages on the matrix cores
+        if (s.hb == 10 && pl->server_mfma) // blocks of 2^25: the inverse stages on the matrix cores
             FO_TRY(launch(pl, KID_SERVER_MFMA, k_server_mfma, dim3((unsigned)pl->ntiles), dim3(1024), st, s));
         else
             FO_TRY((launch_strided<SM_SERVER, true>(pl, KID_SERVER_HIGH, dim3((unsigned)pl->ntiles, 1), st, s, none)));

@@ -550,3 +550,45 @@ def test_negative_amplitudes_flip_the_decoded_vector(env, d, blk, M):
     from tests.parity import rel_l2
     assert rel_l2(g2.cpu().numpy(), want) < 1e-5
     plan.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,M,blk,server_scale", [
+    ((1 << 24) + 12_345, 3, 0, 0),            # n = 2^25, ragged, the theorem's server amplitude
+    ((1 << 25) + 70_001, 2, 25, 1),           # two blocks of 2^25, server amplitude from the measured norm of the mean
+])
+def test_matrix_core_server_pass_equals_the_vector_unit_one(env, monkeypatch, d, M, blk, server_scale):
+    """Blocks of 2^25: the server pass runs its ten inverse stages on the matrix cores (fp16 pieces of exact integers).
+    With FO_SERVER_VECTOR_UNIT=1 a plan keeps the vector-unit kernel.  Every product and sum of the matrix-core form is
+    exact, so the mean, the downlink amplitudes and the downlink bits of the two plans are identical to the bit."""
+    import torch
+    O, B, inputs, dev = env
+    gs = [torch.from_numpy(inputs.heavy_tailed(d, m)).to(dev) for m in range(M)]
+    out = []
+    for vector_unit in (False, True):
+        if vector_unit:
+            monkeypatch.setenv("FO_SERVER_VECTOR_UNIT", "1")
+        else:
+            monkeypatch.delenv("FO_SERVER_VECTOR_UNIT", raising=False)
+        plan = B.Plan(d=d, M=M, block_log2=blk, seed=77, server_scale=server_scale)
+        W, nb, nt = plan.W, plan.nblocks, plan.ntot
+        bits_up = torch.zeros((M, W), dtype=torch.int64, device=dev)
+        lam_up = torch.zeros((M, nb), dtype=torch.float32, device=dev)
+        for m in range(M):
+            plan.fo_encode(gs[m], 3, m, bits_up[m], lam_up[m])
+        bits_down = torch.zeros(W, dtype=torch.int64, device=dev)
+        lam_down = torch.zeros(nb, dtype=torch.float32, device=dev)
+        gbar = torch.zeros(nt, dtype=torch.float32, device=dev)
+        plan.fo_server_aggregate(bits_up, lam_up, 3, bits_down, lam_down, gbar)
+        torch.cuda.synchronize()
+        plan.fo_profile_begin()
+        plan.fo_server_aggregate(bits_up, lam_up, 3, bits_down, lam_down, gbar)
+        torch.cuda.synchronize()
+        kernels = set(plan.fo_profile_end())
+        assert ("k_strided<SERVER>" in kernels) == vector_unit and ("k_server_mfma" in kernels) == (not vector_unit), kernels
+        out.append((bits_down.cpu().numpy(), lam_down.cpu().numpy(), gbar.cpu().numpy().view(np.uint32)))
+        plan.close()
+    assert np.isfinite(out[0][2].view(np.float32)).all() and np.count_nonzero(out[0][2]) > 0.9 * out[0][2].size
+    assert np.array_equal(out[0][1], out[1][1])
+    assert np.array_equal(out[0][2], out[1][2])
+    assert np.array_equal(out[0][0], out[1][0])
