@@ -556,6 +556,7 @@ def test_negative_amplitudes_flip_the_decoded_vector(env, d, blk, M):
 @pytest.mark.parametrize("d,M,blk,server_scale", [
     ((1 << 24) + 12_345, 3, 0, 0),            # n = 2^25, ragged, the theorem's server amplitude
     ((1 << 25) + 70_001, 2, 25, 1),           # two blocks of 2^25, server amplitude from the measured norm of the mean
+    ((1 << 24) + 5, 33, 0, 0),                # an odd, larger number of workers (both parities of the doubled buffers)
 ])
 def test_matrix_core_server_pass_equals_the_vector_unit_one(env, monkeypatch, d, M, blk, server_scale):
     """Blocks of 2^25: the server pass runs its ten inverse stages on the matrix cores (fp16 pieces of exact integers).
