@@ -55,8 +55,9 @@
  * H D_eps gbar = (lambda / M)(2 c - M) and the server needs no transform at all, only the count, the dither
  * and the comparison.  This drops the independence of eps^s that the paper's server lemma assumes; it is a
  * flagged variant, never the default.  gbar_or_null still works (one inverse transform, for checking).
- * Both shared modes are built for transform lengths up to 2^25 and need M b < 2^31 (the summed sign vectors
- * are transformed in 32-bit integers).
+ * Both shared modes need M b < 2^31 (the summed sign vectors are transformed in 32-bit integers).  For transform
+ * lengths above 2^25 (three passes) fo_step measures the workers' norms in a first round of encodes before the
+ * common amplitude is known, i.e. it encodes twice.
  *
  * Averaged downlink quantiser (K > 1).  The server's message is Q_{lambda^s,K} of Def. 3.2: the mean of K
  * one-bit quantisers with independent dithers, which cuts the downlink's error term by K (Lemma "Second

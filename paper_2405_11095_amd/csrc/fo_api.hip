@@ -147,7 +147,6 @@ int plan_geometry(const fo_params &q, fo_plan *pl)
     pl->npass = high == 0 ? 0 : (high <= 10 ? 1 : 2);
     pl->hb[0] = pl->npass == 2 ? (high + 1) / 2 : high;
     pl->hb[1] = high - pl->hb[0];
-    if (q.eps_mode != FO_EPS_INDEPENDENT && pl->npass == 2) return FO_EINVAL; // shared eps: not built for b > 2^25
     // shared eps: the sum of the M sign vectors is transformed in int32, magnitudes up to M b
     if (q.eps_mode != FO_EPS_INDEPENDENT && (uint64_t)q.M * pl->b >= ((uint64_t)1 << 31)) return FO_EINVAL;
     pl->planes = 0;
@@ -306,6 +305,18 @@ extern "C" int fo_step(fo_plan *pl, const float *const *g, float *x, float delta
     int rc = prepare_scales(pl, M, false, pl->scales_up, pl->nblocks, st, &given);
     if (rc) return rc;
     if (pl->npass == 2) {
+        // three-pass transforms are encoded one worker at a time.  With a shared eps the workers must agree on one
+        // amplitude per block before any of them quantises: a first round of encodes only measures the norms (its
+        // messages are overwritten by the second), then the largest amplitude is everybody's.
+        if (pl->p.eps_mode != FO_EPS_INDEPENDENT && !given) {
+            for (uint32_t m = 0; m < M && !rc; ++m)
+                rc = launch_encode(pl, nullptr, g[m], 0, pl->p.d, 1, m, round, false, pl->bits_up + (uint64_t)m * pl->W, 0,
+                                   pl->scales_up + (uint64_t)m * pl->nblocks, 0, pl->buf_a, 0, st);
+            if (rc) return rc;
+            rc = launch_common_scales(pl, st, pl->scales_up, M);
+            if (rc) return rc;
+            given = true;
+        }
         for (uint32_t m = 0; m < M && !rc; ++m)
             rc = launch_encode(pl, nullptr, g[m], 0, pl->p.d, 1, m, round, given, pl->bits_up + (uint64_t)m * pl->W, 0,
                                pl->scales_up + (uint64_t)m * pl->nblocks, 0, pl->buf_a, 0, st);

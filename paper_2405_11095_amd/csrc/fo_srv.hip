@@ -37,6 +37,39 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
         if (!gbar_or_null) return FO_OK;
         // the mean itself was asked for (checking): one inverse transform of the summed sign vectors, below
     }
+    if (pl->p.eps_mode != FO_EPS_INDEPENDENT && pl->npass == 2) {
+        // the same for three-pass transforms (blocks above 2^25): counts -> low stages (int32) -> middle stages -> the
+        // shared pass on the top stages (amplitude, eps, eps^s, forward top stages) -> middle stages forward -> low pass
+        ContigArgs c = contig_base(pl, r);
+        c.src = bits_up; c.src_stride = pl->W; c.M = M;
+        c.scales = const_cast<float *>(scales_up); c.scales_stride = 0;
+        c.party0 = 0; c.eps_party0 = kPartyAllWorkers;
+        c.dst = pl->buf_a; c.dst_stride = 0;
+        const dim3 grid1((unsigned)pl->ntiles, 1), block(kThreads);
+        FO_TRY(launch(pl, KID_COUNT_LOW, (k_contig<IN_COUNT, OUT_I32, false, false, 15>), grid1, block, st, c, none));
+        StridedArgs s0 = strided_base(pl, r, 0);
+        s0.src = pl->buf_a; s0.dst = pl->buf_c;
+        FO_TRY(launch_strided<SM_MID_I32>(pl, KID_DEC_MID, grid1, st, s0, none));
+        StridedArgs s = strided_base(pl, r, 1);
+        s.src = pl->buf_c; s.dst = pl->buf_b;
+        s.scales = scales_up; s.scales_stride = 0;
+        s.gbar = gbar_or_null;
+        s.out_coef = mean_coef; s.eps_party0 = FO_PARTY_SERVER;
+        s.partials = l2s ? pl->partials : nullptr;
+        FO_TRY(launch_strided<SM_SHARED>(pl, KID_SERVER_HIGH, grid1, st, s, none));
+        if (zero_transform) return FO_OK;
+        if (l2s) FO_TRY(finalize_server_scales());
+        StridedArgs s2 = strided_base(pl, r, 0);
+        s2.src = pl->buf_b; s2.dst = pl->buf_c;
+        FO_TRY(launch_strided<SM_MID_F32>(pl, KID_ENC_MID, grid1, st, s2, none));
+        ContigArgs e = contig_base(pl, r);
+        e.src = pl->buf_c; e.dst = bits_down;
+        e.scales = scales_down;
+        e.party0 = FO_PARTY_SERVER; e.eps_party0 = FO_PARTY_SERVER;
+        set_quantiser(e, pl, FO_PARTY_SERVER);
+        FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid1, st, e, none));
+        return FO_OK;
+    }
     if (pl->p.eps_mode != FO_EPS_INDEPENDENT && pl->npass <= 1) {
         // one eps and one amplitude for all workers: sum the packed sign vectors per coordinate (vertical
         // popcount), then a single inverse transform instead of M

@@ -54,7 +54,7 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(scale_rule=0, B=0.0) == B.EINVAL
     assert create(server_scale=2) == B.EINVAL
     assert create(d=(1 << 30) + 1) == B.EINVAL
-    assert create(d=(1 << 26), eps_mode=1) == B.EINVAL          # shared eps is built up to n = 2^25
+    assert create(d=(1 << 26), M=32, eps_mode=1) == B.EINVAL    # the same limit for a three-pass transform (M b = 2^31)
     assert create(d=(1 << 25), M=64, eps_mode=1) == B.EINVAL    # M b = 2^31 would overflow the summed sign vectors
     assert lib.fo_plan_create(None, None) == B.EINVAL
     # NULL plan in the hot calls

@@ -209,6 +209,7 @@ def test_parameter_variants(env, name, kw):
     ("two_pass", (1 << 18) + 11, 7, 0, 1),
     ("blocked_b65536", (1 << 18) + 11, 3, 16, 2),
     ("n2p25", 25_557_032, 3, 0, 1),
+    ("three_pass", (1 << 25) + 5, 2, 0, 1),
 ])
 def test_all_shared_eps_zero_transform_server(env, name, d, M, blk, K):
     """The server shares the workers' eps: its pre-quantisation vector is (lambda / M)(2 c - M) and the kernel
@@ -343,6 +344,7 @@ def test_c4_full_size_sampled_blocks(env, blk):
     ("two_pass", (1 << 18) + 11, 7, 0),
     ("blocked_b65536", (1 << 18) + 11, 5, 16),
     ("n2p25", 25_557_032, 3, 0),
+    ("three_pass", (1 << 25) + 5, 2, 0),
 ])
 def test_shared_worker_eps_popcount_server(env, name, d, M, blk):
     """One eps and one amplitude for all workers: the server sums the packed sign vectors per
