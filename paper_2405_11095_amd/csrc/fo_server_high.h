@@ -24,9 +24,9 @@
 // Every product and sum is an integer multiple of its unit below 2^24 units, so the result equals the
 // vector-unit kernel's bit for bit.
 //
-// 1024 threads.  Global loads take 16 bytes per lane (four lanes cover the 64 bytes of a row, an instruction sixteen
-// rows; one dword = a pair of columns); they are written to LDS as [column pair][rB][rA] and wave w reads column
-// pair w from there in the operand's register order, all with 16-byte accesses.  The staging buffer and the eps
+// 1024 threads.  Global loads are the coalesced ones of the vector-unit kernel (16 lanes cover the 64 bytes of a
+// row, one dword = a pair of columns); they are written to LDS as [column pair][rB][rA] and wave w reads column
+// pair w from there in the operand's register order with 16-byte accesses.  The staging buffer and the eps
 // table are doubled, which leaves one barrier per worker.
 #pragma once
 #include "fo_strided.h"
@@ -80,7 +80,7 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
     // the two constants of the second piece in registers, so that it is one v_and_or_b32
     // (and the -1 of stage B's remainder, so that it stays a multiply-add the compiler can emit as v_fma_mixlo/hi_f16)
     float minus_one = -1.f;
-    asm volatile("" : "+v"(minus_one));
+    asm volatile("" : "+s"(minus_one));
     uint32_t lo_mask = 0x007F007Fu, lo_magic = 0x48004800u;
     asm volatile("" : "+s"(lo_mask));
     asm volatile("" : "+v"(lo_magic));
@@ -90,24 +90,22 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
     if (t < 32u) bias_tab[t] = t < 16u ? 0.f : -(float)((1152 * 128 + 1024) * 32) * 0x1p-9f;
     const float *const bias_mine = bias_tab + (col == 0u ? 16u : 0u);
 
-    // loads, 16 bytes per lane: lane = (four column pairs, rB bits 0..3), wave = (rB bit 4, rA bits 2..4), load q = rA bits 0..1;
-    // four lanes cover the 64 bytes of a row, an instruction sixteen rows
-    const uint32_t cq = lane & 3u, rl = lane >> 2;
+    // loads: lane = (column pair, rB bits 0..1), wave = (rB bits 2..4, rA bit 4), register p = rA bits 0..3
+    const uint32_t cp = lane & 15u, rl = lane >> 4;
     const uint32_t pitch = (1u << kTileLog2) + a.src_pad; // elements between rows
-    const uint32_t rb_mine = rl + 16u * (wave & 1u), ra_mine = 4u * (wave >> 1);
-    const uint32_t ld_off = ((32u * ra_mine + rb_mine) * pitch + 8u * cq) * 2u; // bytes
-    const uint32_t st_word = 4u * cq * kShPairWords + rb_mine * kShRowWords + ra_mine;
+    const uint32_t rb_mine = rl + 4u * (wave & 7u), ra_mine = 16u * (wave >> 3);
+    const uint32_t ld_off = ((32u * ra_mine + rb_mine) * pitch + 2u * cp) * 2u; // bytes
+    const uint32_t st_word = cp * kShPairWords + rb_mine * kShRowWords + ra_mine;
     const uint32_t rd_word = wave * kShPairWords + col * kShRowWords + 4u * h;
-    uint32_t raw[4][4]; // [load = rA bits 0..1][column pair within the lane's four]
-    // A worker's tile is asked for in four parts, spread over the arithmetic of the worker before, so that the
-    // address unit works through them while the vector unit is busy.
+    uint32_t raw[16];
+    // A worker's tile is asked for in four parts (part q = registers 4 q .. 4 q + 3), spread over the arithmetic of the
+    // worker before, so that the address unit works through them while the vector unit is busy.
     auto request = [&](uint32_t m, int q) {
         const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin + (g.origin >> g.ls) * a.src_pad;
         uint32_t off = ld_off;
         asm volatile("" : "+v"(off)); // the zero extension stays next to the loads, which then take the scalar-base form
-        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-        const u32x4 v = ld_uniform<u32x4>(src + (uint64_t)(32u * q) * pitch, off);
-        raw[q][0] = v.x; raw[q][1] = v.y; raw[q][2] = v.z; raw[q][3] = v.w;
+#pragma unroll
+        for (int p = 4 * q; p < 4 * q + 4; ++p) raw[p] = ld_uniform<uint32_t>(src + (uint64_t)(32u * p) * pitch, off);
     };
 
     float acc[2][16];
@@ -135,8 +133,8 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
         uint32_t *const stage = lds + (m & 1u) * kShStageWords;
         uint32_t *const epsm = epsw + (m & 1u) * 1024u;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) // column pair 4 cq + j: four consecutive rA
-            *reinterpret_cast<uint4 *>(stage + st_word + j * kShPairWords) = make_uint4(raw[0][j], raw[1][j], raw[2][j], raw[3][j]);
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<uint4 *>(stage + st_word + 4 * q) = make_uint4(raw[4 * q], raw[4 * q + 1], raw[4 * q + 2], raw[4 * q + 3]);
         // the next worker's amplitude is asked for ahead of its tile: loads complete in order, so waiting for it
         // later does not wait for the tile
         const float lam_now = lam_next;
@@ -253,8 +251,8 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
         const uint2 *const tb = reinterpret_cast<const uint2 *>(lds);
 #pragma unroll
         for (int p = 0; p < 16; ++p) {
-            const uint32_t row = (lane >> 4) | ((uint32_t)p << 2) | (wave << 6);
-            const uint2 d = tb[row * kShTransPitch + (lane & 15u)];
+            const uint32_t row = rl | ((uint32_t)p << 2) | (wave << 6);
+            const uint2 d = tb[row * kShTransPitch + cp];
             mean[2 * p] = __uint_as_float(d.x);
             mean[2 * p + 1] = __uint_as_float(d.y);
         }
