@@ -51,7 +51,7 @@ def main():
     ap.add_argument("--block-log2", type=int, default=None,
                     help="transform length 2^k (default: the workload's first entry; c4 has 10, 12, 14, 16)")
     ap.add_argument("--K", type=int, default=1, help="averaging count of the downlink quantiser")
-    ap.add_argument("--server-scale", default="thm", choices=["thm", "l2"],
+    ap.add_argument("--server-scale", default="thm", choices=["thm", "l2", "sup"],
                     help="server amplitude: Thm 5.5 as stated (default) or from the measured norm of the mean")
     ap.add_argument("--eps-mode", default="independent", choices=["independent", "shared", "all"],
                     help="independent: the paper's protocol (default, the headline number); shared: one eps for all "
@@ -81,7 +81,7 @@ def main():
     eps_mode = {"independent": B.EPS_INDEPENDENT, "shared": B.EPS_SHARED_WORKERS, "all": B.EPS_SHARED_ALL}[args.eps_mode]
     blk = wl["block_log2"][0] if args.block_log2 is None else args.block_log2
     seed = 0xF05D + int(args.workload[1])
-    srv = B.SERVER_SCALE_L2 if args.server_scale == "l2" else B.SERVER_SCALE_THM
+    srv = {"thm": B.SERVER_SCALE_THM, "l2": B.SERVER_SCALE_L2, "sup": B.SERVER_SCALE_SUP}[args.server_scale]
     plan = B.Plan(d=d, M=M, block_log2=blk, K=args.K, seed=seed, eps_mode=eps_mode, server_scale=srv)
     n = plan.ntot
     print(f"[bench] workload {args.workload}: d={d} n={n} M={M}; inputs ready in {time.time() - t0:.1f}s; "

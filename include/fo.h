@@ -38,7 +38,10 @@
  * lambda^s >= alpha_s sqrt(ln b / b) ||gbar||, and FO_SERVER_SCALE_L2 takes exactly that, with the norm of
  * the mean the server has just formed.  It is between sqrt(M) (when the uplink's quantisation noise dominates
  * gbar, the usual case) and alpha sqrt(ln b) times smaller, which cuts the downlink's error term by that
- * factor squared.
+ * factor squared.  With FO_EPS_SHARED_ALL the vector the server quantises is (lambda / M)(2 c - M), bounded by
+ * lambda in every coordinate for every eps, and the quantiser of Def. 3.2 is unbiased whenever the sup norm of its
+ * input is at most its amplitude: FO_SERVER_SCALE_SUP then takes lambda^s = lambda, the workers' common amplitude,
+ * alpha_s sqrt(ln b) times below the theorem's rule (other eps modes reject it with FO_EINVAL).
  *
  * Amplitudes a caller supplies (FO_FORCE_SCALE, fo_decode, fo_server_aggregate) may have either sign: the decoder is
  * linear in them, so a negated amplitude gives the negated vector on every path.
@@ -100,6 +103,7 @@ extern "C" {
 
 #define FO_SERVER_SCALE_THM 0u /* lambda^s = alpha_s max_n lambda_n sqrt(ln b)  (Thm 5.5 as stated)            */
 #define FO_SERVER_SCALE_L2 1u  /* lambda^s = alpha_s sqrt(ln b / b) ||gbar_block||_2 (measured, see "Scales")  */
+#define FO_SERVER_SCALE_SUP 2u /* lambda^s = max_n lambda_n; FO_EPS_SHARED_ALL only (see "Scales")              */
 
 #define FO_PARTY_SERVER 0xFFFFFFFFu /* party id of the server; workers are 0 .. M-1      */
 #define FO_FORCE_SCALE 1u /* fo_encode flag: scales[] is an input (amplitudes to use)    */

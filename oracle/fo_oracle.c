@@ -42,6 +42,7 @@
 #define ORC_EPS_SHARED_ALL 2u
 #define ORC_SERVER_SCALE_THM 0u
 #define ORC_SERVER_SCALE_L2 1u
+#define ORC_SERVER_SCALE_SUP 2u /* all-shared eps only: lambda^s = the workers' common amplitude */
 
 typedef struct {
     uint64_t d;          /* logical gradient length                                  */
@@ -346,7 +347,7 @@ void orc_decode(const orc_params *p, const int32_t *q, const double *lam, uint32
 /* ------------------------------------------------------------------------------------------ */
 
 /* Server amplitude of Thm 5.5, per block: lambda^s = alpha_s * lambda * sqrt(log n) with
- * lambda the largest worker amplitude of that block. */
+ * lambda the largest worker amplitude of that block (or lambda itself, rule SUP, see below). */
 void orc_server_lambda(const orc_params *p, const double *lam_up, double *lam_s)
 {
     uint64_t b, nb, ntot;
@@ -358,7 +359,11 @@ void orc_server_lambda(const orc_params *p, const double *lam_up, double *lam_s)
         /* a NaN amplitude must poison the result the way it poisons a sum */
         for (uint32_t n = 0; n < p->M; ++n)
             if (lam_up[(uint64_t)n * nb + j] != lam_up[(uint64_t)n * nb + j]) m = NAN;
-        lam_s[j] = p->alpha_s * m * sqrt(log((double)b));
+        /* All-shared eps: the vector the server quantises is (lambda / M)(2 c - M), at most lambda in every
+         * coordinate whatever eps is, and the quantiser of Def. 3.2 is unbiased as soon as ||z||_inf <= lambda^s
+         * (first moment of the quantiser, Appendix): the amplitude lambda itself is then admissible. */
+        if (p->server_scale == ORC_SERVER_SCALE_SUP) lam_s[j] = m;
+        else lam_s[j] = p->alpha_s * m * sqrt(log((double)b));
     }
 }
 

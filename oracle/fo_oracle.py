@@ -21,7 +21,7 @@ PARTY_SERVER = 0xFFFFFFFF
 DITHER_UNIFORM, DITHER_NONE = 0, 1
 SCALE_BOUND, SCALE_L2 = 0, 1
 EPS_INDEPENDENT, EPS_SHARED_WORKERS, EPS_SHARED_ALL = 0, 1, 2
-SERVER_SCALE_THM, SERVER_SCALE_L2 = 0, 1
+SERVER_SCALE_THM, SERVER_SCALE_L2, SERVER_SCALE_SUP = 0, 1, 2
 DOMAIN_EPS, DOMAIN_DITHER = 1, 2
 
 

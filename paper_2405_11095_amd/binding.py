@@ -17,7 +17,7 @@ OK, EINVAL, EALIGN, EHIP, ENOMEM, ESIZE = 0, -1, -2, -3, -4, -5
 DITHER_UNIFORM, DITHER_NONE = 0, 1
 SCALE_BOUND, SCALE_L2 = 0, 1
 EPS_INDEPENDENT, EPS_SHARED_WORKERS, EPS_SHARED_ALL = 0, 1, 2
-SERVER_SCALE_THM, SERVER_SCALE_L2 = 0, 1
+SERVER_SCALE_THM, SERVER_SCALE_L2, SERVER_SCALE_SUP = 0, 1, 2
 PARTY_SERVER = 0xFFFFFFFF
 FORCE_SCALE = 1
 MAX_WORKERS = 64

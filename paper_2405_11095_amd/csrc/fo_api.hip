@@ -114,7 +114,10 @@ int plan_geometry(const fo_params &q, fo_plan *pl)
         return FO_EINVAL;
     if (!(q.alpha >= 2.f) || !(q.alpha_s >= 2.f)) return FO_EINVAL;
     if (q.scale_rule == FO_SCALE_BOUND && !(q.B > 0.f)) return FO_EINVAL;
-    if (q.server_scale != FO_SERVER_SCALE_THM && q.server_scale != FO_SERVER_SCALE_L2) return FO_EINVAL;
+    if (q.server_scale != FO_SERVER_SCALE_THM && q.server_scale != FO_SERVER_SCALE_L2 && q.server_scale != FO_SERVER_SCALE_SUP)
+        return FO_EINVAL;
+    // lambda^s = lambda is admissible only where the server's vector is bounded by lambda surely
+    if (q.server_scale == FO_SERVER_SCALE_SUP && q.eps_mode != FO_EPS_SHARED_ALL) return FO_EINVAL;
 
     pl->p = q;
     pl->stats = nullptr;
@@ -157,7 +160,7 @@ int plan_geometry(const fo_params &q, fo_plan *pl)
     pl->coef_lambda = (float)((double)q.alpha * std::sqrt(std::log(bd) / bd));
     pl->sqrtb = (float)std::sqrt(bd);
     pl->rsqrtb = (float)(1.0 / std::sqrt(bd));
-    pl->coef_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd)));
+    pl->coef_s = q.server_scale == FO_SERVER_SCALE_SUP ? 1.f : (float)((double)q.alpha_s * std::sqrt(std::log(bd)));
     pl->coef_lambda_s = (float)((double)q.alpha_s * std::sqrt(std::log(bd) / bd));
     return FO_OK;
 }

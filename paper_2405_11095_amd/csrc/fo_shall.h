@@ -110,8 +110,11 @@ static __global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
     for (int s = 0; s < 4; ++s) {
         const uint64_t w = 4 * q + s;
         const uint64_t j = w < a.W ? ((w * 64u + lane) >> a.logb) : 0;
-        val[s] = a.lam[j] * (float)(2 * c[s] - (int32_t)a.M) * (a.sqrtb / (float)a.M);
-        thr[s] = a.lam_s[j] * a.sqrtb * 5.9604644775390625e-08f; // 2^-24: u = m 2^-24 with m odd
+        // (2 c - M) / M is exactly +-1 when all workers agree, and lambda sqrt(b) is the very product the threshold
+        // below forms when lambda^s = lambda (FO_SERVER_SCALE_SUP): a coordinate at the bound then keeps its sign for
+        // every dither
+        val[s] = (a.lam[j] * a.sqrtb) * ((float)(2 * c[s] - (int32_t)a.M) / (float)a.M);
+        thr[s] = (a.lam_s[j] * a.sqrtb) * 5.9604644775390625e-08f; // 2^-24: u = m 2^-24 with m odd
         cnt[s] = 0u;
     }
     for (uint32_t k = 0; k < a.K; ++k) {

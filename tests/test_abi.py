@@ -52,7 +52,9 @@ def test_bad_parameters_are_rejected_on_the_host(lib):
     assert create(dither=7) == B.EINVAL and create(scale_rule=9) == B.EINVAL and create(eps_mode=3) == B.EINVAL
     assert create(alpha=1.5) == B.EINVAL and create(alpha_s=float("nan")) == B.EINVAL
     assert create(scale_rule=0, B=0.0) == B.EINVAL
-    assert create(server_scale=2) == B.EINVAL
+    assert create(server_scale=3) == B.EINVAL
+    # lambda^s = lambda is admissible only when the server shares the workers' eps
+    assert create(server_scale=2, eps_mode=0) == B.EINVAL and create(server_scale=2, eps_mode=1) == B.EINVAL
     assert create(d=(1 << 30) + 1) == B.EINVAL
     assert create(d=(1 << 26), M=32, eps_mode=1) == B.EINVAL    # the same limit for a three-pass transform (M b = 2^31)
     assert create(d=(1 << 25), M=64, eps_mode=1) == B.EINVAL    # M b = 2^31 would overflow the summed sign vectors

@@ -223,6 +223,24 @@ def test_all_shared_eps_zero_transform_server(env, name, d, M, blk, K):
     gates(rep)
 
 
+@pytest.mark.parametrize("name,d,M,blk,K", [
+    ("single_pass", 30_000, 5, 0, 1),
+    ("blocked", 200_003, 4, 12, 3),
+    ("two_pass", (1 << 18) + 11, 7, 0, 1),
+    ("blocked_b65536", (1 << 18) + 11, 3, 16, 2),
+])
+def test_all_shared_eps_with_the_workers_amplitude_for_the_server(env, name, d, M, blk, K):
+    """FO_SERVER_SCALE_SUP: with the server sharing the workers' eps its vector is bounded by lambda in every
+    coordinate, so lambda^s = lambda is admissible (Def. 3.2's first-moment lemma); amplitudes, downlink bits, decode
+    and update against the oracle's long way round, and the coordinates that sit at the bound included."""
+    O, B, inputs, dev = env
+    gs = [inputs.heavy_tailed(d, m) for m in range(M)]
+    rep = check_round_trip(O, B, gs, d=d, M=M, block_log2=blk, seed=0x99 + M, rnd=17, delta=0.02, device=dev,
+                           eps_mode=B.EPS_SHARED_ALL, K=K, server_scale=B.SERVER_SCALE_SUP)
+    print(name, rep, flush=True)
+    gates(rep)
+
+
 @pytest.mark.parametrize("d,blk,eps_mode", [(20_000, 0, 0), (50_000, 0, 0), (300_000, 0, 0), (70_000, 10, 0),
                                             (200_000, 16, 1), (5_000, 7, 2)])
 def test_worker_message_decode(env, d, blk, eps_mode):
@@ -595,3 +613,28 @@ def test_matrix_core_server_pass_equals_the_vector_unit_one(env, monkeypatch, d,
     assert np.array_equal(out[0][1], out[1][1])
     assert np.array_equal(out[0][2], out[1][2])
     assert np.array_equal(out[0][0], out[1][0])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("d,blk", [(100_000, 0), (40_000, 9)])
+def test_unanimous_workers_pass_the_bound_exactly(env, d, blk):
+    """FO_SERVER_SCALE_SUP puts unanimous coordinates exactly at the quantiser's bound: (lambda / M)(2 c - M) = +-lambda
+    with lambda^s = lambda.  The dither is an odd multiple of 2^-24 inside (-1, 1), so such a coordinate keeps its
+    sign for every draw: all-ones messages come back all ones, all-zero messages all zero, in every round."""
+    import torch
+    O, B, inputs, dev = env
+    M = 5
+    plan = B.Plan(d=d, M=M, block_log2=blk, seed=31, eps_mode=B.EPS_SHARED_ALL, server_scale=B.SERVER_SCALE_SUP)
+    W, nb = plan.W, plan.nblocks
+    lam = torch.rand(nb, dtype=torch.float32, device=dev) + 0.25
+    lam_up = lam.repeat(M, 1).contiguous()
+    for fill in (-1, 0):
+        bits_up = torch.full((M, W), fill, dtype=torch.int64, device=dev)
+        for rnd in range(40):
+            bits_down = torch.full((W,), 0x5555, dtype=torch.int64, device=dev)
+            lam_s = torch.zeros(nb, dtype=torch.float32, device=dev)
+            plan.fo_server_aggregate(bits_up, lam_up, rnd, bits_down, lam_s)
+            torch.cuda.synchronize()
+            assert torch.equal(lam_s, lam)
+            assert bool((bits_down == fill).all()), (fill, rnd)
+    plan.close()

@@ -383,6 +383,45 @@ def test_all_shared_eps_server_identity_and_unbiasedness(oracle):
     assert np.max(np.abs(mean - want)) < 5.0 * lam_s / math.sqrt(R)
 
 
+def test_all_shared_eps_admits_the_workers_amplitude_for_the_server(oracle):
+    """Rule SUP (all-shared eps only): lambda^s = lambda.  The server's vector (lam / M)(2 c - M) is bounded by lam
+    in every coordinate, so (i) nothing is ever clipped, (ii) the quantiser stays unbiased (first-moment lemma of
+    Def. 3.2: E Q = z whenever ||z||_inf <= lambda^s), checked by Monte Carlo over rounds, and (iii) the decoded
+    message's error drops by the factor alpha_s^2 ln n of the theorem's rule: with K = 1 every decoded coordinate
+    has magnitude lambda^s, so E ||g^d - mean||^2 = n (lambda^s)^2 - ||w||^2 (second-moment lemma)."""
+    d, M = 64, 3
+    ps = oracle.params(d=d, M=M, seed=190, eps_mode=oracle.EPS_SHARED_ALL, server_scale=oracle.SERVER_SCALE_SUP)
+    pt = oracle.params(d=d, M=M, seed=190, eps_mode=oracle.EPS_SHARED_ALL)
+    gs = [np.random.default_rng(191 + m).standard_normal(d).astype(np.float32) for m in range(M)]
+    lam = np.array([0.9])
+    bits, lams = _uplink(oracle, ps, gs, 7, lam=lam)
+    s, st = oracle.server(ps, bits, lams, 7, want_margin=True), oracle.server(pt, bits, lams, 7)
+    assert s["lam_s"][0] == 0.9 and np.isclose(st["lam_s"][0], 2.0 * 0.9 * math.sqrt(math.log(d)), rtol=1e-13)
+    assert np.array_equal(s["gbar"], st["gbar"])
+    c = sum((oracle.unpack(b, d) > 0).astype(np.int64) for b in bits)
+    w = (0.9 / M) * (2 * c - M)
+    assert np.max(np.abs(w)) <= 0.9
+    u = np.asarray(oracle.dither_u(ps.seed, 7, 0xFFFFFFFF, 0, np.arange(d))).reshape(d)
+    assert np.allclose(s["margin"], w + 0.9 * u, atol=1e-12)
+    # coordinates at the bound are quantised deterministically: |u| < 1, so sign(w + lam u) = sign(w)
+    at_bound = np.abs(w) == 0.9
+    assert np.array_equal(np.sign(s["margin"][at_bound]), np.sign(w[at_bound]))
+    R = 4000
+    want = np.mean([g.astype(np.float64) for g in gs], axis=0)
+    mean_s, err_s, err_t = np.zeros(d), 0.0, 0.0
+    for rnd in range(R):
+        o = oracle.round_trip(ps, gs, np.zeros(d), 1.0, rnd, want=True)
+        mean_s += o["gd"] / R
+        err_s += float(np.sum((o["gd"] - o["gbar"][:d]) ** 2)) / R
+        lam_s = o["lam_s"][0]
+        if rnd < 400:
+            ot = oracle.round_trip(pt, gs, np.zeros(d), 1.0, rnd, want=True)
+            err_t += float(np.sum((ot["gd"] - ot["gbar"][:d]) ** 2)) / 400
+    assert np.max(np.abs(mean_s - want)) < 5.0 * lam_s / math.sqrt(R)
+    # downlink error: n lam_s^2 - ||w||^2 on average, against n (alpha_s^2 ln n) lam^2 - ||w||^2 for the theorem's rule
+    assert err_s < d * lam_s ** 2 and err_t > 0.5 * (4.0 * math.log(d)) * err_s
+
+
 def test_measured_norm_server_amplitude(oracle):
     """Server rule L2: lambda^s = alpha_s sqrt(ln n / n) ||gbar||, per block; it is the smallest amplitude the
     server lemma of Thm 5.5 admits, never larger than the theorem's rule (||gbar|| <= lambda sqrt(n)), and the
