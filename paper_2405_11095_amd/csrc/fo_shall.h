@@ -21,6 +21,34 @@ struct ShallArgs {
     float sqrtb;               // the kernels compare in the unnormalised domain: values and thresholds times sqrt(b)
 };
 
+// Vertical count for the 256 coordinates (four packed words 4 q .. 4 q + 3) of a wave: c[s] = number of workers whose
+// bit of coordinate 64 s + lane is set.  Lane l first counts the four coordinates of nibble (l & 15) of word (l >> 4):
+// the nibble times 0x00204081 has its four bits in the low bit of four bytes, so one add per worker counts four
+// coordinates (M <= 64 < 256: no byte overflows); eight lanes read the same 32-bit half word.  Then the byte counts
+// move to the lanes of their coordinates: coordinate 64 s + j sits in lane 16 s + j / 4, byte j % 4.
+__device__ __forceinline__ void shall_counts(const ShallArgs &a, uint64_t q, uint32_t lane, int32_t (&c)[4])
+{
+    const uint64_t w = 4 * q + (lane >> 4);
+    const uint32_t *const halves = reinterpret_cast<const uint32_t *>(a.bits_up);
+    const uint32_t sh = (lane & 7u) * 4u;
+    uint32_t cnt = 0u;
+    if (w < a.W) {
+        const uint32_t *const mine = halves + 2 * w + ((lane >> 3) & 1u);
+        for (uint32_t m0 = 0; m0 < a.M; m0 += 8u) { // eight workers' loads in flight at a time
+            uint32_t h[8];
+#pragma unroll
+            for (uint32_t k = 0; k < 8u; ++k) h[k] = (m0 + k < a.M) ? mine[2 * (uint64_t)(m0 + k) * a.W] : 0u;
+#pragma unroll
+            for (uint32_t k = 0; k < 8u; ++k) cnt += __umul24((h[k] >> sh) & 15u, 0x00204081u) & 0x01010101u;
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const uint32_t v = (uint32_t)__builtin_amdgcn_ds_bpermute((int)((16u * s + (lane >> 2)) * 4u), (int)cnt);
+        c[s] = (int32_t)((v >> ((lane & 3u) * 8u)) & 255u);
+    }
+}
+
 // ---- measured-norm server amplitude for this mode: ||gbar_block||^2 = (lambda / M)^2 sum_i (2 c_i - M)^2, and the
 // sum is an integer, so it is accumulated exactly (and in any order) with 64-bit integer atomics.
 static __global__ void k_zero_u64(unsigned long long *p, uint64_t n)
@@ -36,20 +64,7 @@ static __global__ __launch_bounds__(256) void k_shall_sumsq(const ShallArgs a, u
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const uint64_t q = (uint64_t)blockIdx.x * 4u + wave;
     int32_t c[4] = { 0, 0, 0, 0 };
-    if (4 * q < a.W) {
-        for (uint32_t m0 = 0; m0 < a.M; m0 += 16u) {
-            const uint32_t m = m0 + (lane >> 2);
-            const uint64_t w = 4 * q + (lane & 3u);
-            const uint64_t mine = (m < a.M && w < a.W) ? a.bits_up[(uint64_t)m * a.W + w] : 0ull;
-            const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
-#pragma unroll
-            for (int i = 0; i < 64; ++i) {
-                const uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine_hi, i) << 32) |
-                                      (uint32_t)__builtin_amdgcn_readlane((int)mine_lo, i);
-                c[i & 3] += __builtin_amdgcn_inverse_ballot_w64(word) ? 1 : 0;
-            }
-        }
-    }
+    if (4 * q < a.W) shall_counts(a, q, lane, c);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
         const bool live = 4 * q + s < a.W;
@@ -89,21 +104,8 @@ static __global__ __launch_bounds__(256) void k_shall(const ShallArgs a)
     if (4 * q >= a.W) return;
     uint32_t rk1, rlo;
     resolve_round(a.k1, a.round_lo, a.round_dev, rk1, rlo);
-    // vertical count: sixteen workers at a time, lane l fetches word (l & 3) of worker (l >> 2) (one coalesced
-    // load), then every fetched word is broadcast and each lane adds its own bit of it
-    int32_t c[4] = { 0, 0, 0, 0 };
-    for (uint32_t m0 = 0; m0 < a.M; m0 += 16u) {
-        const uint32_t m = m0 + (lane >> 2);
-        const uint64_t w = 4 * q + (lane & 3u);
-        const uint64_t mine = (m < a.M && w < a.W) ? a.bits_up[(uint64_t)m * a.W + w] : 0ull;
-        const uint32_t mine_lo = (uint32_t)mine, mine_hi = (uint32_t)(mine >> 32);
-#pragma unroll
-        for (int i = 0; i < 64; ++i) {
-            const uint64_t word = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)mine_hi, i) << 32) |
-                                  (uint32_t)__builtin_amdgcn_readlane((int)mine_lo, i);
-            c[i & 3] += __builtin_amdgcn_inverse_ballot_w64(word) ? 1 : 0;
-        }
-    }
+    int32_t c[4];
+    shall_counts(a, q, lane, c);
     float val[4], thr[4];
     uint32_t cnt[4];
 #pragma unroll
