@@ -77,8 +77,8 @@ static __global__ __launch_bounds__(1024) void k_server_mfma(const StridedArgs a
             const uint32_t k = 8u * (2u * mm + (e >> 2)) + 4u * h + (e & 3u);
             bh[mm][e] = (_Float16)(parity32(k & col) ? -0.25f : 0.25f);
         }
-    // the two constants of the second piece in registers, so that it is one v_and_or_b32
-    // (and the -1 of stage B's remainder, so that it stays a multiply-add the compiler can emit as v_fma_mixlo/hi_f16)
+    // Constants the compiler must not fold: the -1 of stage B's remainder (so that value - piece stays a multiply-add
+    // and becomes v_fma_mixlo/hi_f16) and the two constants of stage A's second piece (one v_and_or_b32 from registers).
     float minus_one = -1.f;
     asm volatile("" : "+s"(minus_one));
     uint32_t lo_mask = 0x007F007Fu, lo_magic = 0x48004800u;
