@@ -136,15 +136,37 @@ int launch_server(fo_plan *pl, const uint64_t *bits_up, const float *scales_up, 
                              pl->buf_a, 0, st);
     }
     if (pl->npass == 2) {
-        // three-pass transforms: unfused (decode each worker into the mean, then a plain encode)
-        float *gbar = gbar_or_null ? gbar_or_null : pl->buf_b;
-        for (uint32_t m = 0; m < M; ++m) {
-            int rc = launch_decode(pl, bits_up + (uint64_t)m * pl->W, scales_up + (uint64_t)m * pl->nblocks, round, m, gbar,
-                                   pl->ntot, m == 0 ? STORE_SET : STORE_ACC, mean_coef, 0.f, pl->buf_a, st);
-            if (rc) return rc;
-        }
-        return launch_encode(pl, nullptr, gbar, 0, pl->ntot, 1, FO_PARTY_SERVER, round, !l2s, bits_down, 0, scales_down, 0,
-                             pl->buf_a, 0, st);
+        // three-pass transforms (blocks above 2^25): low stages of all workers (bits -> int32), the middle stages in
+        // place, one fused pass on the top stages that forms the mean and starts the re-encode, the middle stages
+        // forward, the low pass that dithers and packs
+        const dim3 gridM((unsigned)pl->ntiles, M), grid1((unsigned)pl->ntiles, 1), block(kThreads);
+        ContigArgs c = contig_base(pl, r);
+        c.src = bits_up; c.src_stride = pl->W;
+        c.dst = pl->buf_a; c.dst_stride = pl->ntot;
+        FO_TRY(launch(pl, KID_DEC_LOW, (k_contig<IN_BITS, OUT_I32, false, false, 15>), gridM, block, st, c, none));
+        StridedArgs s0 = strided_base(pl, r, 0);
+        s0.src = pl->buf_a; s0.src_stride = pl->ntot;
+        s0.dst = pl->buf_a; s0.dst_stride = pl->ntot; // in place: a workgroup reads its whole tile before it writes it
+        FO_TRY(launch_strided<SM_MID_I32>(pl, KID_DEC_MID, gridM, st, s0, none));
+        StridedArgs s = strided_base(pl, r, 1);
+        s.src = pl->buf_a; s.src_stride = pl->ntot;
+        s.dst = pl->buf_b;
+        s.scales = scales_up; s.scales_stride = pl->nblocks;
+        s.gbar = gbar_or_null;
+        s.M = M; s.out_coef = 2.f * mean_coef; s.eps_party0 = FO_PARTY_SERVER; // the decode side carries half values
+        s.partials = l2s ? pl->partials : nullptr;
+        FO_TRY((launch_strided<SM_SERVER, false>(pl, KID_SERVER_HIGH, grid1, st, s, none)));
+        if (l2s) FO_TRY(finalize_server_scales());
+        StridedArgs s2 = strided_base(pl, r, 0);
+        s2.src = pl->buf_b; s2.dst = pl->buf_c;
+        FO_TRY(launch_strided<SM_MID_F32>(pl, KID_ENC_MID, grid1, st, s2, none));
+        ContigArgs e = contig_base(pl, r);
+        e.src = pl->buf_c; e.dst = bits_down;
+        e.scales = scales_down;
+        e.party0 = FO_PARTY_SERVER; e.eps_party0 = FO_PARTY_SERVER;
+        set_quantiser(e, pl, FO_PARTY_SERVER);
+        FO_TRY(launch_pack<IN_F32>(pl, KID_ENC_LOW, grid1, st, e, none));
+        return FO_OK;
     }
     // two-pass transforms: M low-stage passes (bits -> int32), one fused high-stage pass that forms the mean
     // and starts the re-encode, one low-stage pass that dithers and packs

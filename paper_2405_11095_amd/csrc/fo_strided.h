@@ -491,10 +491,35 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
                 flip_pair(acc[2 * p], acc[2 * p + 1], epsw[(ut_out >> 5) + (upair_out(p) >> 5)] >> eshift);
             }
         } else {
-        static_assert(MODE != SM_SERVER || IN16, "the server pass reads the int16 intermediate");
-        uint32_t raw[kSP]; // packed tile of the next worker, in flight while the current one is transformed
 #pragma unroll
         for (int r = 0; r < kSV; ++r) acc[r] = 0.f;
+        if constexpr (!IN16) {
+            // int32 intermediate (three-pass transforms, blocks above 2^25): the values outgrow fp32's 24 bits, so the
+            // remaining stages stay in integers, as in the decoder, and only the result is converted; no prefetch.
+            for (uint32_t m = 0; m < a.M; ++m) {
+                int32_t v[kSV];
+                load_int(v, static_cast<const char *>(a.src) + ((uint64_t)m * a.src_stride + g.origin) * 4u);
+                const RngKey key_eps = { a.k0, rk1, kDomainEps, rlo, m };
+                uint32_t *const epsm = epsw + (m & 1u) * kEpsWords; // two tables in turn, as below
+                fill_eps<L::T>(epsm, g, key_eps, t);
+                stages_a<int32_t, LV>(v, cb);
+                if (need_x) {
+                    __syncthreads(); // the previous worker's exchange buffer is no longer read
+                    exchange_wide<int32_t, LV>(v, xbuf, lane, wave);
+                    stages_b<int32_t, LV>(v, cb);
+                } else {
+                    __syncthreads(); // publishes the eps table
+                }
+                const uint32_t cbits = __float_as_uint(a.scales[(uint64_t)m * a.scales_stride + gb] * a.out_coef);
+#pragma unroll
+                for (int p = 0; p < kSP; ++p) {
+                    const uint32_t w = epsm[(ut_out >> 5) + (upair_out(p) >> 5)];
+                    acc[2 * p] = fmaf((float)v[2 * p], __uint_as_float(((w >> eshift) << 31) + cbits), acc[2 * p]);
+                    acc[2 * p + 1] = fmaf((float)v[2 * p + 1], __uint_as_float(((w >> (eshift + 1u)) << 31) + cbits), acc[2 * p + 1]);
+                }
+            }
+        } else {
+        uint32_t raw[kSP]; // packed tile of the next worker, in flight while the current one is transformed
         const uint32_t otp = ota + (uta >> cb) * a.src_pad;
         auto request = [&](uint32_t m) {
             const int16_t *src = static_cast<const int16_t *>(a.src) + (uint64_t)m * a.src_stride + g.origin + (g.origin >> g.ls) * a.src_pad;
@@ -543,6 +568,7 @@ __global__ __launch_bounds__(SL<LV>::T, 4) void k_strided(const StridedArgs a, c
             process(m, std::true_type{});
         }
         process(a.M - 1, std::false_type{});
+        }
         }
         server_reencode<LV, WIDE>(acc, a, g, tile, rk1, rlo, xbuf, epsw, red, need_x);
     }

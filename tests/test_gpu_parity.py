@@ -50,6 +50,8 @@ CASES = [
     # (server tiles of the second block start 2^25 coordinates up), the second partly filled
     ("n2p25_single_worker", (1 << 24) + 1, 1, 0, "gaussian"),
     ("blocked_b2p25_two_blocks", (1 << 25) + 300_001, 2, 25, "gaussian"),
+    # three passes (n = 2^26) with several workers: the fused server over the int32 intermediates
+    ("three_pass_three_workers", (1 << 25) + 77, 3, 0, "heavy"),
 ]
 
 
