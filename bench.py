@@ -162,7 +162,6 @@ def main():
         "k_server_mfma": M * 4 * n + 4 * n,
         "k_contig<IN_COUNT>": M * W8 + 4 * n,
         "k_mean_mfma": M * W8 + 4 * n,
-        "k_server_tile": M * W8 + W8,
         "k_shall": M * W8 + W8,
         "k_strided<DEC_LAST>": 4 * n + 8 * d,
         "k_contig<IN_GRAD,OUT_PACK>": M * (4 * d + W8) + (4 * n + W8 if "k_mean_mfma" in per_kernel else 0),
