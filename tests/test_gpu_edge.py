@@ -535,10 +535,12 @@ def test_resume_needs_only_x_and_the_round(env):
     second.close()
 
 
-@pytest.mark.parametrize("d,blk,M", [(50_000, 12, 3), (30_000, 0, 2), ((1 << 17) + 9, 16, 2), (300_000, 0, 3)])
+@pytest.mark.parametrize("d,blk,M", [(50_000, 12, 3), (30_000, 0, 2), ((1 << 17) + 9, 16, 2), (300_000, 0, 3),
+                                     ((1 << 24) + 3, 0, 2), ((1 << 25) + 3, 0, 2)])
 def test_negative_amplitudes_flip_the_decoded_vector(env, d, blk, M):
     """The decoder is linear in the amplitude, D = lambda D_eps H^T q (Def. 3.8): a caller-supplied negative
-    amplitude gives minus the vector of the positive one on every kernel path (single tile, pair, two-pass), and in
+    amplitude gives minus the vector of the positive one on every kernel path (single tile, pair, two-pass, the
+    matrix-core server pass of n = 2^25, three-pass), and in
     the server's mean a worker with a negated amplitude enters with the opposite sign."""
     import torch
     O, B, inputs, dev = env
